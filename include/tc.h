@@ -1,0 +1,150 @@
+/*
+ * tc.h — C ABI of the MI355X (gfx950) mixed-batch paged-attention library.
+ *
+ * One serving iteration on one GPU instance runs a *mixed batch*: one chunk of a
+ * prompt at some chunk offset plus the running decode requests, piggybacked into
+ * the same iteration (paper Sec. 2.2 "PD Aggregation", Sec. 3.2 hybrid-mode
+ * inference); the instances of the system differ only in the chunk size they run
+ * (Sec. 3.1).  Per layer the iteration (1) stores the new tokens' key and value
+ * vectors in the KV cache (Sec. 2.1: K and V are cached; Sec. 3.5: paged memory)
+ * and (2) computes scaled dot-product attention of every query token over all
+ * tokens of its own sequence so far (Sec. 2.1).  This library is those two steps.
+ *
+ * All pointers marked DEVICE are GPU memory owned by the caller; all pointers
+ * marked HOST are host memory owned by the caller and may be reused as soon as the
+ * call returns.  `stream` is a hipStream_t passed as void* (NULL = default stream).
+ * Every call returns a tc_status; nothing throws, aborts or prints.  After a
+ * validation error nothing was launched.  Calls are asynchronous on `stream`.
+ *
+ * Tensor element type is bf16 (16-bit patterns).  Layouts, with B = block_size = 16,
+ * D = head_dim, Hq / Hkv = query / KV heads, G = Hq / Hkv:
+ *   q, out        [T][Hq][D]      packed query rows of the batch, T = q_start[num_seqs]
+ *   k_new, v_new  [T][Hkv][D]     keys / values of the same rows
+ *   k_pool        [num_blocks][Hkv][D/8][B][8]
+ *   v_pool        [num_blocks][Hkv][D][B]
+ * Token j of sequence s lives in pool block block_table[s][j / B], slot j % B.
+ * Query head h reads KV head h / G.
+ */
+#ifndef TC_H
+#define TC_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    TC_OK = 0,
+    TC_ERR_NULL = 1,      /* a required pointer is NULL                                            */
+    TC_ERR_SHAPE = 2,     /* unsupported Hq / Hkv / head_dim / block_size / dtype / num_blocks     */
+    TC_ERR_SPAN = 3,      /* q_start not increasing, a sequence with no query token, negative ctx  */
+    TC_ERR_BLOCK = 4,     /* a used table entry outside [0, num_blocks), or max_blocks too small   */
+    TC_ERR_WORKSPACE = 5, /* workspace NULL or smaller than tc_plan_workspace_bytes()              */
+    TC_ERR_DEVICE = 6,    /* a HIP call failed; text in tc_last_error()                            */
+    TC_ERR_ARG = 7        /* any other bad argument (sequence index out of range, ...)             */
+} tc_status;
+
+#define TC_BF16 1
+
+/* Shape of the paged KV pool and where it lives. */
+typedef struct {
+    int32_t num_q_heads;  /* Hq,  multiple of num_kv_heads, G = Hq/Hkv <= 16 */
+    int32_t num_kv_heads; /* Hkv */
+    int32_t head_dim;     /* 64 or 128 */
+    int32_t block_size;   /* 16 */
+    int32_t dtype;        /* TC_BF16 */
+    int64_t num_blocks;   /* blocks in each pool, num_blocks * 16 < 2^31 */
+    void *k_pool;         /* DEVICE [num_blocks][Hkv][D/8][16][8] bf16; may be NULL for tc_plan_create* */
+    void *v_pool;         /* DEVICE [num_blocks][Hkv][D][16] bf16                                        */
+} tc_kv_pool;
+
+/*
+ * One mixed batch (paper Sec. 2.2 / 3.2): sequence s owns packed query rows
+ * [q_start[s], q_start[s+1]); ctx_len[s] tokens of it are already cached (for a
+ * prefill chunk this is the chunk offset).  A sequence with one query row is a
+ * decode, with more it is a prefill chunk; any mix is accepted.  Row i of sequence
+ * s sits at absolute position ctx_len[s] + i and attends over positions 0..that.
+ * Only the first ceil((ctx_len[s] + q_len[s]) / 16) entries of a table row are read.
+ */
+typedef struct {
+    int32_t num_seqs;
+    const int32_t *q_start;     /* HOST [num_seqs + 1], q_start[0] = 0, strictly increasing */
+    const int32_t *ctx_len;     /* HOST [num_seqs], >= 0                                    */
+    const int32_t *block_table; /* HOST [num_seqs][max_blocks]                              */
+    int32_t max_blocks;
+} tc_batch;
+
+/* Opaque per-iteration plan: validated descriptors plus the device work list
+ * (prefill tiles, decode KV splits, merge map).  One plan serves every layer of
+ * the iteration.  Owned by the library; free with tc_plan_destroy. */
+typedef struct tc_plan tc_plan;
+
+typedef struct {
+    int32_t num_seqs, total_q;          /* S, T                                              */
+    int32_t num_prefill_seqs, num_decode_seqs;
+    int32_t num_prefill_items;          /* workgroups of the prefill branch                  */
+    int32_t num_decode_items;           /* wave-sized KV splits of the decode branch         */
+    int32_t num_merge_items;            /* (sequence, KV head) pairs that need the merge     */
+    int32_t num_partials;               /* split partials held in the workspace              */
+    int32_t split_tokens;               /* KV tokens per decode split                        */
+    int32_t rows_per_prefill_item;      /* (position, head) rows per prefill workgroup       */
+    int32_t grid_blocks, block_threads; /* launch shape of the fused attention kernel        */
+    int64_t total_pages;                /* table entries copied                              */
+} tc_plan_info;
+
+/* Validate the batch against the pool shape, build the work list and upload it on
+ * `stream` (one host-to-device copy).  pool->k_pool / v_pool are not touched.
+ * An empty batch (num_seqs == 0) gives a valid plan whose calls are no-ops. */
+tc_status tc_plan_create(const tc_kv_pool *pool, const tc_batch *batch, void *stream, tc_plan **out);
+
+/* Same validation and work list, host side only (no GPU needed, nothing uploaded).
+ * Such a plan can be inspected but the compute calls reject it with TC_ERR_ARG. */
+tc_status tc_plan_create_host(const tc_kv_pool *pool, const tc_batch *batch, tc_plan **out);
+
+tc_status tc_plan_get_info(const tc_plan *plan, tc_plan_info *info);
+
+/* Copy work items to HOST memory for inspection: kind 0 = prefill, 1 = decode,
+ * 2 = merge; 8 int32 per item, at most cap_items items.  Fields:
+ *   prefill {seq, kv_head, first_local_pos, num_pos, q_row0, ctx, page_off, num_pages}
+ *   decode  {seq, kv_head, kv_begin, kv_end, q_row, partial_slot (-1 = writes out), page_off, 0}
+ *   merge   {seq, kv_head, q_row, first_partial_slot, num_splits, 0, 0, 0}                  */
+tc_status tc_plan_copy_items(const tc_plan *plan, int32_t kind, int32_t *dst, size_t cap_items);
+
+/* Bytes of DEVICE scratch tc_mixed_attention needs for this plan (may be 0). */
+size_t tc_plan_workspace_bytes(const tc_plan *plan);
+
+void tc_plan_destroy(tc_plan *plan);
+
+/* KV-cache append (paper Sec. 2.1, Sec. 3.5): for row i of sequence s and KV head h,
+ * pool[block_table[s][(ctx+i)/16]][h] slot (ctx+i)%16 <- k_new / v_new [q_start[s]+i][h][:].
+ * Bit copy; every other pool byte is left untouched.  k_new, v_new: DEVICE. */
+tc_status tc_kv_append(const tc_plan *plan, const tc_kv_pool *pool, const void *k_new, const void *v_new,
+                       void *stream);
+
+/* Mixed-batch attention (paper Sec. 2.1 scaled dot-product attention over the cached
+ * tokens; Sec. 2.2 chunk + piggybacked decodes): out[t][h] = softmax_j(scale * q[t][h] . k_j) v_j
+ * over j = 0..p of the row's sequence, read from the pool as it is when the kernel runs, so
+ * tc_kv_append of the same batch must precede it on the same stream.  Prefill chunks and
+ * decode tokens are processed by one kernel launch; sequences whose KV range was split get
+ * their partial results combined by a small second launch.  fp32 accumulation, bf16 output
+ * rounded to nearest even.  q, out, workspace: DEVICE.  Results are bitwise reproducible
+ * for a fixed plan. */
+tc_status tc_mixed_attention(const tc_plan *plan, const tc_kv_pool *pool, const void *q, void *out, float scale,
+                             void *workspace, size_t workspace_bytes, void *stream);
+
+/* Test hook: un-paged copy of tokens 0..ctx+q_len-1 of sequence `seq` out of the pool,
+ * k_out / v_out DEVICE [kv_len][Hkv][D] bf16. */
+tc_status tc_kv_gather(const tc_plan *plan, const tc_kv_pool *pool, int32_t seq, void *k_out, void *v_out,
+                       void *stream);
+
+const char *tc_status_str(tc_status s);
+/* Text of the last error raised on the calling thread ("" if none). */
+const char *tc_last_error(void);
+int32_t tc_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* TC_H */

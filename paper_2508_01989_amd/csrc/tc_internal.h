@@ -1,0 +1,66 @@
+// Internal declarations shared by the host-side planner, the C ABI glue and the
+// kernel launchers of the gfx950 mixed-batch attention library.
+#pragma once
+#include <cstddef>
+#include <cstdint>
+#include <string>
+#include <vector>
+
+#include "tc.h"
+
+namespace tc {
+
+constexpr int kBlock = 16;          // tokens per KV page
+constexpr int kWgThreads = 512;     // threads per workgroup of the fused attention kernel
+constexpr int kWgWaves = kWgThreads / 64;
+constexpr int kPrefillRows = 256;   // (position, head) rows per prefill workgroup: 32 per wave
+constexpr int kItemInts = 8;        // int32 fields per work item
+constexpr int kMaxSplitPages = 64;  // a decode split's page ids fit one wavefront register
+
+// Field indices of work items (see tc_plan_copy_items in tc.h).
+enum { PF_SEQ, PF_KVH, PF_POS0, PF_NPOS, PF_QROW0, PF_CTX, PF_PAGEOFF, PF_NPAGES };
+enum { DC_SEQ, DC_KVH, DC_BEGIN, DC_END, DC_QROW, DC_SLOT, DC_PAGEOFF, DC_PAD };
+enum { MG_SEQ, MG_KVH, MG_QROW, MG_SLOT0, MG_NSPLIT };
+
+void set_error(const std::string &msg);
+
+}  // namespace tc
+
+struct tc_plan {
+    int Hq = 0, Hkv = 0, D = 0, G = 0;
+    int64_t num_blocks = 0;
+    int S = 0, T = 0;
+    int n_prefill_seqs = 0, n_decode_seqs = 0;
+    int n_prefill = 0, n_decode = 0, n_merge = 0, n_partials = 0;
+    int split_tokens = 0;
+    int64_t total_pages = 0;
+    std::vector<int32_t> q_start, ctx_len, page_off;  // host copies
+    // One int32 buffer uploaded as a whole; offsets (in int32 units) of its sections.
+    std::vector<int32_t> host;
+    size_t off_slot = 0, off_pages = 0, off_prefill = 0, off_decode = 0, off_merge = 0;
+    int32_t *dev = nullptr;  // device copy of `host`, nullptr for host-only plans
+    int device = -1;
+
+    int grid_blocks() const { return n_prefill + (n_decode + tc::kWgWaves - 1) / tc::kWgWaves; }
+    size_t workspace_bytes() const {
+        // per partial: G heads x (D accumulators + running max + running sum), fp32
+        return (size_t)n_partials * (size_t)G * (size_t)(D + 2) * sizeof(float);
+    }
+};
+
+namespace tc {
+
+// Validate and build the host side of a plan.  Returns TC_OK or an error (text via set_error).
+tc_status build_plan(const tc_kv_pool *pool, const tc_batch *batch, tc_plan **out);
+tc_status check_pool_matches(const tc_plan *plan, const tc_kv_pool *pool, bool need_ptrs);
+
+// Kernel launchers (tc_kernels.hip).  All return hipError_t as int (0 = success).
+int launch_kv_append(const tc_plan *p, const tc_kv_pool *pool, const void *k_new, const void *v_new, void *stream);
+int launch_kv_gather(const tc_plan *p, const tc_kv_pool *pool, int seq, void *k_out, void *v_out, void *stream);
+int launch_attention(const tc_plan *p, const tc_kv_pool *pool, const void *q, void *out, float scale,
+                     void *workspace, void *stream);
+int upload_plan(tc_plan *p, void *stream);
+void free_plan_device(tc_plan *p);
+const char *hip_error_text(int err);
+
+}  // namespace tc

@@ -1,0 +1,562 @@
+// gfx950 kernels of the mixed-batch paged-attention path and their launchers.
+//
+//   kv_append_kernel   scatter this iteration's K/V rows into the paged pools      (HBM-bound)
+//   kv_gather_kernel   un-paged copy of one sequence (test hook)                   (HBM-bound)
+//   mixed_attention_kernel  ONE launch per layer for the whole mixed batch
+//       (paper Sec. 2.2: a prompt chunk plus piggybacked decodes share an iteration):
+//         workgroups [0, n_prefill)      causal chunked-prefill tiles, MFMA 32x32x16 bf16
+//         remaining workgroups           8 independent wavefronts, one decode KV split
+//                                        each, MFMA 16x16x32 bf16
+//   split_merge_kernel combine the split partials of long decode sequences
+//
+// Both attention branches compute S^T = K Q^T and O^T = V^T P^T so that the
+// probabilities a lane produces are exactly the B operand it must feed to the second
+// MFMA (no cross-lane movement), and the per-row softmax state is one scalar per lane.
+// The pool layouts (K: [D/8][16][8], V: [D][16] per block and KV head) are the MFMA
+// A-operand layouts of those two products, so K/V go from memory to the matrix cores
+// without any transposition.
+#include <hip/hip_runtime.h>
+
+#include "tc_internal.h"
+
+namespace tc {
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+
+struct AttnArgs {
+    const uint16_t *k_pool, *v_pool, *q;
+    uint16_t *out;
+    const int32_t *pages;    // page ids of all sequences, CSR by sequence
+    const int32_t *prefill;  // work items
+    const int32_t *decode;
+    float *ws_o;             // [n_partials][G][D]
+    float *ws_ml;            // [n_partials][G][2]  (running max in the log2 domain, running sum)
+    int n_prefill, n_decode;
+    int Hq, Hkv, G;
+    float scale_log2;        // softmax scale times log2(e)
+};
+
+__device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
+
+__device__ __forceinline__ float xor_lanes(float v, int mask) { return __shfl_xor(v, mask, 64); }
+
+// ------------------------------------------------------------------------------------
+// KV append / gather
+// ------------------------------------------------------------------------------------
+// One thread moves 8 consecutive head-dim elements (16 bytes) of K and of V of one
+// (token, KV head).  K keeps the 8 elements together; V is stored token-minor, so its 8
+// elements go to 8 rows of the [D][16] tile.
+template <int D>
+__global__ void __launch_bounds__(256) kv_append_kernel(uint16_t *__restrict__ k_pool, uint16_t *__restrict__ v_pool,
+                                                        const uint16_t *__restrict__ k_new,
+                                                        const uint16_t *__restrict__ v_new,
+                                                        const int32_t *__restrict__ slot_of_row, int T, int Hkv) {
+    constexpr int CH = D / 8;
+    const int64_t gid = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    const int64_t total = (int64_t)T * Hkv * CH;
+    if (gid >= total) return;
+    const int c = (int)(gid % CH);
+    const int h = (int)((gid / CH) % Hkv);
+    const int t = (int)(gid / ((int64_t)CH * Hkv));
+    const int slot = slot_of_row[t];
+    const int64_t blk = slot / kBlock;
+    const int tok = slot % kBlock;
+    const int64_t src = ((int64_t)t * Hkv + h) * D + c * 8;
+    const u32x4 kv = *reinterpret_cast<const u32x4 *>(k_new + src);
+    const u32x4 vv = *reinterpret_cast<const u32x4 *>(v_new + src);
+    const int64_t tile = (blk * Hkv + h) * (int64_t)(kBlock * D);
+    *reinterpret_cast<u32x4 *>(k_pool + tile + ((int64_t)c * kBlock + tok) * 8) = kv;
+    uint16_t *vdst = v_pool + tile + (int64_t)(c * 8) * kBlock + tok;
+#pragma unroll
+    for (int e = 0; e < 8; e++) {
+        const uint32_t w = vv[e >> 1];
+        vdst[e * kBlock] = (uint16_t)((e & 1) ? (w >> 16) : (w & 0xFFFFu));
+    }
+}
+
+template <int D>
+__global__ void __launch_bounds__(256) kv_gather_kernel(const uint16_t *__restrict__ k_pool,
+                                                        const uint16_t *__restrict__ v_pool,
+                                                        const int32_t *__restrict__ pages, int kv_len, int Hkv,
+                                                        uint16_t *__restrict__ k_out, uint16_t *__restrict__ v_out) {
+    constexpr int CH = D / 8;
+    const int64_t gid = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    const int64_t total = (int64_t)kv_len * Hkv * CH;
+    if (gid >= total) return;
+    const int c = (int)(gid % CH);
+    const int h = (int)((gid / CH) % Hkv);
+    const int j = (int)(gid / ((int64_t)CH * Hkv));
+    const int64_t blk = pages[j / kBlock];
+    const int tok = j % kBlock;
+    const int64_t tile = (blk * Hkv + h) * (int64_t)(kBlock * D);
+    const int64_t dst = ((int64_t)j * Hkv + h) * D + c * 8;
+    *reinterpret_cast<u32x4 *>(k_out + dst) = *reinterpret_cast<const u32x4 *>(k_pool + tile + ((int64_t)c * kBlock + tok) * 8);
+    const uint16_t *vsrc = v_pool + tile + (int64_t)(c * 8) * kBlock + tok;
+    u32x4 vv;
+#pragma unroll
+    for (int e = 0; e < 4; e++) vv[e] = (uint32_t)vsrc[(2 * e) * kBlock] | ((uint32_t)vsrc[(2 * e + 1) * kBlock] << 16);
+    *reinterpret_cast<u32x4 *>(v_out + dst) = vv;
+}
+
+// ------------------------------------------------------------------------------------
+// Prefill branch: one workgroup = 256 (position, head) rows of one KV head, 32 per wave.
+// ------------------------------------------------------------------------------------
+// Row R of the workgroup is position first_pos + R / G, query head kv_head * G + R % G.
+// The KV range 0..last position is swept in 64-token tiles (four pages); each tile is
+// copied page by page into LDS exactly as it lies in the pool and consumed by
+//   S^T[token][row]  = sum_d K[token][d] Q[row][d]        (A = K from LDS, B = Q in registers)
+//   O^T[d][row]     += sum_token V^T[d][token] P^T[token][row]   (A = V^T from LDS, B = P)
+// with the online softmax (running max m, running sum l) kept per row in fp32.
+template <int D>
+struct PrefillCfg {
+    static constexpr int kTileTokens = 64;
+    static constexpr int kTilePages = kTileTokens / kBlock;
+    static constexpr int kPageBytes = kBlock * D * 2;               // one (page, KV head) tile of K or of V
+    static constexpr int kTileBytes = kTilePages * kPageBytes;      // K part or V part of one LDS stage
+    static constexpr int kPieces = kTileBytes / 16 / kWgThreads;    // 16-byte pieces per thread per tensor
+    static constexpr int kLdsBytes = 2 * 2 * kTileBytes;            // two stages of K and V
+};
+
+template <int D>
+__device__ __forceinline__ void prefill_fetch(const AttnArgs &A, const int32_t *__restrict__ pages, int n_pages,
+                                              int kv_len, int kvh, int tile, u32x4 (&kr)[PrefillCfg<D>::kPieces],
+                                              u32x4 (&vr)[PrefillCfg<D>::kPieces]) {
+    using C = PrefillCfg<D>;
+    constexpr int kPiecesPerPage = C::kPageBytes / 16;
+#pragma unroll
+    for (int i = 0; i < C::kPieces; i++) {
+        const int x = threadIdx.x + i * kWgThreads;
+        const int b = x / kPiecesPerPage;
+        const int off = x % kPiecesPerPage;
+        const int page = tile * C::kTilePages + b;
+        u32x4 kk = {0u, 0u, 0u, 0u}, vv = {0u, 0u, 0u, 0u};
+        if (page < n_pages) {
+            const int64_t base = ((int64_t)pages[page] * A.Hkv + kvh) * (int64_t)(kBlock * D);
+            kk = *reinterpret_cast<const u32x4 *>(A.k_pool + base + (int64_t)off * 8);
+            vv = *reinterpret_cast<const u32x4 *>(A.v_pool + base + (int64_t)off * 8);
+            // Slots past the sequence's last token hold undefined bits; they get probability 0
+            // but must still be finite for the MFMA, so zero them in V.
+            const int n_valid = kv_len - page * kBlock;
+            if (n_valid < kBlock) {
+                const int tok0 = (off & 1) * 8;
+#pragma unroll
+                for (int e = 0; e < 4; e++) {
+                    uint32_t w = vv[e];
+                    if (tok0 + 2 * e >= n_valid) w &= 0xFFFF0000u;
+                    if (tok0 + 2 * e + 1 >= n_valid) w &= 0x0000FFFFu;
+                    vv[e] = w;
+                }
+            }
+        }
+        kr[i] = kk;
+        vr[i] = vv;
+    }
+}
+
+template <int D>
+__device__ __forceinline__ void prefill_stash(char *lds_k, char *lds_v, const u32x4 (&kr)[PrefillCfg<D>::kPieces],
+                                              const u32x4 (&vr)[PrefillCfg<D>::kPieces]) {
+    using C = PrefillCfg<D>;
+#pragma unroll
+    for (int i = 0; i < C::kPieces; i++) {
+        const int x = threadIdx.x + i * kWgThreads;
+        *reinterpret_cast<u32x4 *>(lds_k + x * 16) = kr[i];
+        *reinterpret_cast<u32x4 *>(lds_v + x * 16) = vr[i];
+    }
+}
+
+template <int D>
+__device__ void prefill_item(const AttnArgs &A, const int32_t *__restrict__ it, char *lds) {
+    using C = PrefillCfg<D>;
+    constexpr int KS = D / 16;  // k-steps of the QK^T product
+    constexpr int MT = D / 32;  // 32-row tiles of O^T
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int n = lane & 31, hh = lane >> 5;
+    const int kvh = it[PF_KVH], pos0 = it[PF_POS0], npos = it[PF_NPOS], qrow0 = it[PF_QROW0], ctx = it[PF_CTX];
+    const int n_pages = it[PF_NPAGES];
+    const int32_t *pages = A.pages + it[PF_PAGEOFF];
+    const int G = A.G;
+    const int n_rows = npos * G;
+    const int R = wave * 32 + n;
+    const bool row_valid = R < n_rows;
+    const int Rc = row_valid ? R : n_rows - 1;
+    const int pl = pos0 + Rc / G;
+    const int p_abs = ctx + pl;  // this lane's row attends over tokens 0..p_abs
+    const int64_t row_off = ((int64_t)(qrow0 + pl) * A.Hq + kvh * G + Rc % G) * D;
+    // wave-uniform bounds of the rows this wave owns
+    const int r_lo = min(wave * 32, n_rows - 1), r_hi = min(wave * 32 + 31, n_rows - 1);
+    const int wave_pmin = ctx + pos0 + r_lo / G, wave_pmax = ctx + pos0 + r_hi / G;
+    const int kv_len = ctx + pos0 + npos;  // tokens this workgroup may read (all appended already)
+    const int n_tiles = (kv_len - 1) / C::kTileTokens + 1;
+
+    bf16x8 qreg[KS];
+#pragma unroll
+    for (int kk = 0; kk < KS; kk++) qreg[kk] = *reinterpret_cast<const bf16x8 *>(A.q + row_off + (2 * kk + hh) * 8);
+
+    f32x16 o[MT];
+#pragma unroll
+    for (int c = 0; c < MT; c++)
+#pragma unroll
+        for (int r = 0; r < 16; r++) o[c][r] = 0.f;
+    float m_run = -1e30f, l_run = 0.f;
+
+    u32x4 kr[C::kPieces], vr[C::kPieces];
+    prefill_fetch<D>(A, pages, n_pages, kv_len, kvh, 0, kr, vr);
+    prefill_stash<D>(lds, lds + 2 * C::kTileBytes, kr, vr);
+    __syncthreads();
+
+    for (int tile = 0; tile < n_tiles; tile++) {
+        const int cur = tile & 1;
+        const char *ks = lds + cur * C::kTileBytes;
+        const char *vs = lds + 2 * C::kTileBytes + cur * C::kTileBytes;
+        const bool more = tile + 1 < n_tiles;
+        if (more) prefill_fetch<D>(A, pages, n_pages, kv_len, kvh, tile + 1, kr, vr);
+
+        const int tok0 = tile * C::kTileTokens;
+        if (tok0 <= wave_pmax) {  // otherwise every (row, token) pair of this wave is masked
+            f32x16 s[2];
+#pragma unroll
+            for (int mt = 0; mt < 2; mt++) {
+#pragma unroll
+                for (int r = 0; r < 16; r++) s[mt][r] = 0.f;
+                const char *kp = ks + (2 * mt + (n >> 4)) * C::kPageBytes + (n & 15) * 16;
+#pragma unroll
+                for (int kk = 0; kk < KS; kk++) {
+                    const bf16x8 a = *reinterpret_cast<const bf16x8 *>(kp + (2 * kk + hh) * (kBlock * 16));
+                    s[mt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qreg[kk], s[mt], 0, 0, 0);
+                }
+            }
+            const bool need_mask = tok0 + C::kTileTokens - 1 > wave_pmin;
+            float mx = -1e30f;
+#pragma unroll
+            for (int mt = 0; mt < 2; mt++)
+#pragma unroll
+                for (int r = 0; r < 16; r++) {
+                    float v = s[mt][r] * A.scale_log2;
+                    if (need_mask) {
+                        const int j = tok0 + 32 * mt + 8 * (r >> 2) + 4 * hh + (r & 3);
+                        v = (j <= p_abs) ? v : -INFINITY;
+                    }
+                    s[mt][r] = v;
+                    mx = fmaxf(mx, v);
+                }
+            mx = fmaxf(mx, xor_lanes(mx, 32));
+            const float m_new = fmaxf(m_run, mx);
+            const float alpha = fast_exp2(m_run - m_new);
+            m_run = m_new;
+            float psum = 0.f;
+#pragma unroll
+            for (int mt = 0; mt < 2; mt++)
+#pragma unroll
+                for (int r = 0; r < 16; r++) {
+                    const float pv = fast_exp2(s[mt][r] - m_new);
+                    s[mt][r] = pv;
+                    psum += pv;
+                }
+            l_run = l_run * alpha + psum;
+#pragma unroll
+            for (int c = 0; c < MT; c++)
+#pragma unroll
+                for (int r = 0; r < 16; r++) o[c][r] *= alpha;
+#pragma unroll
+            for (int b = 0; b < C::kTilePages; b++) {
+                bf16x8 pb;
+#pragma unroll
+                for (int e = 0; e < 8; e++) pb[e] = (__bf16)s[b >> 1][8 * (b & 1) + e];
+#pragma unroll
+                for (int c = 0; c < MT; c++) {
+                    const char *vp = vs + b * C::kPageBytes + (32 * c + n) * (kBlock * 2) + hh * 8;
+                    const bf16x4 lo = *reinterpret_cast<const bf16x4 *>(vp);
+                    const bf16x4 hi = *reinterpret_cast<const bf16x4 *>(vp + 16);
+                    const bf16x8 a = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+                    o[c] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, pb, o[c], 0, 0, 0);
+                }
+            }
+        }
+        if (more) prefill_stash<D>(lds + (cur ^ 1) * C::kTileBytes, lds + 2 * C::kTileBytes + (cur ^ 1) * C::kTileBytes, kr, vr);
+        __syncthreads();
+    }
+
+    l_run += xor_lanes(l_run, 32);
+    const float inv = 1.f / l_run;
+    if (row_valid) {
+#pragma unroll
+        for (int c = 0; c < MT; c++)
+#pragma unroll
+            for (int q4 = 0; q4 < 4; q4++) {
+                bf16x4 w;
+#pragma unroll
+                for (int e = 0; e < 4; e++) w[e] = (__bf16)(o[c][4 * q4 + e] * inv);
+                *reinterpret_cast<bf16x4 *>(A.out + row_off + 32 * c + 8 * q4 + 4 * hh) = w;
+            }
+    }
+}
+
+// ------------------------------------------------------------------------------------
+// Decode branch: one wavefront = one (sequence, KV head, KV split); all G query heads of
+// the group ride in the N dimension of the MFMA so K/V are read once per KV head.
+// ------------------------------------------------------------------------------------
+// Lane l: head column j = l % 16, token group g = l / 16.  Per page:
+//   S^T[token][head] = sum_d K[token][d] Q[head][d]   16x16x32, D/32 steps; lane gets tokens 4g..4g+3
+//   O^T[d][head]    += sum_token V^T[d][token] P^T[token][head]   contraction over the 32 tokens
+//                      of a page pair: lane feeds tokens 4g..4g+3 of either page
+template <int D>
+__device__ void decode_item(const AttnArgs &A, const int32_t *__restrict__ it) {
+    constexpr int KS = D / 32;  // k-steps of K Q^T
+    constexpr int MT = D / 16;  // 16-row tiles of O^T
+    const int lane = threadIdx.x & 63;
+    const int j = lane & 15, g = lane >> 4;
+    const int kvh = it[DC_KVH], t0 = it[DC_BEGIN], t1 = it[DC_END], qrow = it[DC_QROW], slot = it[DC_SLOT];
+    const int G = A.G;
+    const int page0 = t0 / kBlock;
+    const int n_pg = (t1 - t0 + kBlock - 1) / kBlock;  // 1..64
+    const int32_t *pages = A.pages + it[DC_PAGEOFF] + page0;
+    const int my_page = pages[min(lane, n_pg - 1)];
+
+    bf16x8 qreg[KS];
+    const int64_t q_off = ((int64_t)qrow * A.Hq + kvh * G + min(j, G - 1)) * D;
+#pragma unroll
+    for (int kk = 0; kk < KS; kk++) {
+        u32x4 w = *reinterpret_cast<const u32x4 *>(A.q + q_off + (4 * kk + g) * 8);
+        if (j >= G) w = u32x4{0u, 0u, 0u, 0u};
+        qreg[kk] = __builtin_bit_cast(bf16x8, w);
+    }
+
+    f32x4 o[MT];
+#pragma unroll
+    for (int c = 0; c < MT; c++) o[c] = f32x4{0.f, 0.f, 0.f, 0.f};
+    float m_run = -1e30f, l_run = 0.f;
+    const int64_t tile_elems = (int64_t)kBlock * D;
+
+    for (int pp = 0; pp < n_pg; pp += 2) {
+        const bool has1 = pp + 1 < n_pg;
+        const int id0 = __builtin_amdgcn_readlane(my_page, pp);
+        const int id1 = __builtin_amdgcn_readlane(my_page, has1 ? pp + 1 : pp);
+        const uint16_t *kb[2] = {A.k_pool + ((int64_t)id0 * A.Hkv + kvh) * tile_elems,
+                                 A.k_pool + ((int64_t)id1 * A.Hkv + kvh) * tile_elems};
+        const uint16_t *vb[2] = {A.v_pool + ((int64_t)id0 * A.Hkv + kvh) * tile_elems,
+                                 A.v_pool + ((int64_t)id1 * A.Hkv + kvh) * tile_elems};
+        bf16x8 kreg[2][KS];
+        u32x2 vreg[2][MT];
+#pragma unroll
+        for (int b = 0; b < 2; b++) {
+#pragma unroll
+            for (int kk = 0; kk < KS; kk++)
+                kreg[b][kk] = *reinterpret_cast<const bf16x8 *>(kb[b] + ((4 * kk + g) * kBlock + j) * 8);
+#pragma unroll
+            for (int c = 0; c < MT; c++)
+                vreg[b][c] = *reinterpret_cast<const u32x2 *>(vb[b] + (16 * c + j) * kBlock + 4 * g);
+        }
+        f32x4 s[2];
+        float mx = -1e30f;
+#pragma unroll
+        for (int b = 0; b < 2; b++) {
+            s[b] = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int kk = 0; kk < KS; kk++) s[b] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kreg[b][kk], qreg[kk], s[b], 0, 0, 0);
+            // tokens of this page still inside the split (<= 0 for the phantom second page)
+            const int n_valid = (b == 1 && !has1) ? 0 : t1 - (t0 + (pp + b) * kBlock);
+#pragma unroll
+            for (int r = 0; r < 4; r++) {
+                float v = s[b][r] * A.scale_log2;
+                v = (4 * g + r < n_valid) ? v : -INFINITY;
+                s[b][r] = v;
+                mx = fmaxf(mx, v);
+            }
+            if (n_valid < kBlock) {  // undefined slots must not reach the MFMA as NaN
+#pragma unroll
+                for (int c = 0; c < MT; c++) {
+                    u32x2 w = vreg[b][c];
+                    if (4 * g + 0 >= n_valid) w[0] &= 0xFFFF0000u;
+                    if (4 * g + 1 >= n_valid) w[0] &= 0x0000FFFFu;
+                    if (4 * g + 2 >= n_valid) w[1] &= 0xFFFF0000u;
+                    if (4 * g + 3 >= n_valid) w[1] &= 0x0000FFFFu;
+                    vreg[b][c] = w;
+                }
+            }
+        }
+        mx = fmaxf(mx, xor_lanes(mx, 16));
+        mx = fmaxf(mx, xor_lanes(mx, 32));
+        const float m_new = fmaxf(m_run, mx);
+        const float alpha = fast_exp2(m_run - m_new);
+        m_run = m_new;
+        bf16x8 pb;
+        float psum = 0.f;
+#pragma unroll
+        for (int b = 0; b < 2; b++)
+#pragma unroll
+            for (int r = 0; r < 4; r++) {
+                const float pv = fast_exp2(s[b][r] - m_new);
+                psum += pv;
+                pb[4 * b + r] = (__bf16)pv;
+            }
+        l_run = l_run * alpha + psum;
+#pragma unroll
+        for (int c = 0; c < MT; c++) {
+            o[c] *= alpha;
+            const u32x4 aw = {vreg[0][c][0], vreg[0][c][1], vreg[1][c][0], vreg[1][c][1]};
+            o[c] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, aw), pb, o[c], 0, 0, 0);
+        }
+    }
+    l_run += xor_lanes(l_run, 16);
+    l_run += xor_lanes(l_run, 32);
+    if (j >= G) return;
+    if (slot < 0) {
+        const float inv = 1.f / l_run;
+        uint16_t *dst = A.out + ((int64_t)qrow * A.Hq + kvh * G + j) * D + 4 * g;
+#pragma unroll
+        for (int c = 0; c < MT; c++) {
+            bf16x4 w;
+#pragma unroll
+            for (int e = 0; e < 4; e++) w[e] = (__bf16)(o[c][e] * inv);
+            *reinterpret_cast<bf16x4 *>(dst + 16 * c) = w;
+        }
+    } else {
+        float *dst = A.ws_o + ((int64_t)slot * G + j) * D + 4 * g;
+#pragma unroll
+        for (int c = 0; c < MT; c++) *reinterpret_cast<f32x4 *>(dst + 16 * c) = o[c];
+        if (g == 0) {
+            float *ml = A.ws_ml + ((int64_t)slot * G + j) * 2;
+            ml[0] = m_run;
+            ml[1] = l_run;
+        }
+    }
+}
+
+template <int D>
+__global__ void __launch_bounds__(kWgThreads) mixed_attention_kernel(const AttnArgs A) {
+    extern __shared__ __align__(16) char lds[];
+    if ((int)blockIdx.x < A.n_prefill) {
+        prefill_item<D>(A, A.prefill + (int64_t)blockIdx.x * kItemInts, lds);
+    } else {
+        const int idx = ((int)blockIdx.x - A.n_prefill) * kWgWaves + (int)(threadIdx.x >> 6);
+        if (idx < A.n_decode) decode_item<D>(A, A.decode + (int64_t)idx * kItemInts);
+    }
+}
+
+// ------------------------------------------------------------------------------------
+// Split-KV merge: out = sum_i 2^(m_i - m*) o_i / sum_i 2^(m_i - m*) l_i, splits in index order.
+// One workgroup per (sequence, KV head); one thread per (head, 4 head-dim elements).
+// ------------------------------------------------------------------------------------
+template <int D>
+__global__ void __launch_bounds__(256) split_merge_kernel(const int32_t *__restrict__ items, const float *__restrict__ ws_o,
+                                                          const float *__restrict__ ws_ml, uint16_t *__restrict__ out,
+                                                          int Hq, int G) {
+    const int32_t *it = items + (int64_t)blockIdx.x * kItemInts;
+    const int kvh = it[MG_KVH], qrow = it[MG_QROW], slot0 = it[MG_SLOT0], ns = it[MG_NSPLIT];
+    constexpr int QD = D / 4;
+    for (int x = threadIdx.x; x < G * QD; x += blockDim.x) {
+        const int j = x / QD, d4 = x % QD;
+        float m_star = -1e30f;
+        for (int i = 0; i < ns; i++) m_star = fmaxf(m_star, ws_ml[((int64_t)(slot0 + i) * G + j) * 2]);
+        f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+        float den = 0.f;
+        for (int i = 0; i < ns; i++) {
+            const int64_t row = (int64_t)(slot0 + i) * G + j;
+            const float w = fast_exp2(ws_ml[row * 2] - m_star);
+            den += w * ws_ml[row * 2 + 1];
+            const f32x4 oi = *reinterpret_cast<const f32x4 *>(ws_o + row * D + d4 * 4);
+            acc += oi * w;
+        }
+        const float inv = 1.f / den;
+        bf16x4 w4;
+#pragma unroll
+        for (int e = 0; e < 4; e++) w4[e] = (__bf16)(acc[e] * inv);
+        *reinterpret_cast<bf16x4 *>(out + ((int64_t)qrow * Hq + kvh * G + j) * D + d4 * 4) = w4;
+    }
+}
+
+// ------------------------------------------------------------------------------------
+// Launchers
+// ------------------------------------------------------------------------------------
+const char *hip_error_text(int err) { return hipGetErrorString((hipError_t)err); }
+
+int upload_plan(tc_plan *p, void *stream) {
+    hipError_t e = hipGetDevice(&p->device);
+    if (e != hipSuccess) return (int)e;
+    const size_t bytes = p->host.size() * sizeof(int32_t);
+    e = hipMalloc((void **)&p->dev, bytes);
+    if (e != hipSuccess) { p->dev = nullptr; return (int)e; }
+    e = hipMemcpyAsync(p->dev, p->host.data(), bytes, hipMemcpyHostToDevice, (hipStream_t)stream);
+    return (int)e;
+}
+
+void free_plan_device(tc_plan *p) {
+    if (p->dev) (void)hipFree(p->dev);
+    p->dev = nullptr;
+}
+
+int launch_kv_append(const tc_plan *p, const tc_kv_pool *pool, const void *k_new, const void *v_new, void *stream) {
+    if (p->T == 0) return 0;
+    const int64_t total = (int64_t)p->T * p->Hkv * (p->D / 8);
+    const unsigned blocks = (unsigned)((total + 255) / 256);
+    hipStream_t st = (hipStream_t)stream;
+    if (p->D == 128)
+        kv_append_kernel<128><<<blocks, 256, 0, st>>>((uint16_t *)pool->k_pool, (uint16_t *)pool->v_pool, (const uint16_t *)k_new,
+                                                     (const uint16_t *)v_new, p->dev + p->off_slot, p->T, p->Hkv);
+    else
+        kv_append_kernel<64><<<blocks, 256, 0, st>>>((uint16_t *)pool->k_pool, (uint16_t *)pool->v_pool, (const uint16_t *)k_new,
+                                                    (const uint16_t *)v_new, p->dev + p->off_slot, p->T, p->Hkv);
+    return (int)hipGetLastError();
+}
+
+int launch_kv_gather(const tc_plan *p, const tc_kv_pool *pool, int seq, void *k_out, void *v_out, void *stream) {
+    const int kv_len = p->ctx_len[seq] + (p->q_start[seq + 1] - p->q_start[seq]);
+    const int64_t total = (int64_t)kv_len * p->Hkv * (p->D / 8);
+    const unsigned blocks = (unsigned)((total + 255) / 256);
+    hipStream_t st = (hipStream_t)stream;
+    const int32_t *pages = p->dev + p->off_pages + p->page_off[seq];
+    if (p->D == 128)
+        kv_gather_kernel<128><<<blocks, 256, 0, st>>>((const uint16_t *)pool->k_pool, (const uint16_t *)pool->v_pool, pages, kv_len,
+                                                     p->Hkv, (uint16_t *)k_out, (uint16_t *)v_out);
+    else
+        kv_gather_kernel<64><<<blocks, 256, 0, st>>>((const uint16_t *)pool->k_pool, (const uint16_t *)pool->v_pool, pages, kv_len,
+                                                    p->Hkv, (uint16_t *)k_out, (uint16_t *)v_out);
+    return (int)hipGetLastError();
+}
+
+template <int D>
+static int launch_attention_d(const tc_plan *p, const AttnArgs &A, hipStream_t st) {
+    static bool lds_ok = false;  // opt in to more than 64 KiB of dynamic LDS once per process
+    const int lds = PrefillCfg<D>::kLdsBytes;
+    if (!lds_ok) {
+        hipError_t e = hipFuncSetAttribute((const void *)mixed_attention_kernel<D>, hipFuncAttributeMaxDynamicSharedMemorySize, lds);
+        if (e != hipSuccess) return (int)e;
+        lds_ok = true;
+    }
+    const int grid = p->grid_blocks();
+    if (grid > 0) mixed_attention_kernel<D><<<grid, kWgThreads, p->n_prefill > 0 ? lds : 0, st>>>(A);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return (int)e;
+    if (p->n_merge > 0)
+        split_merge_kernel<D><<<p->n_merge, 256, 0, st>>>(p->dev + p->off_merge, A.ws_o, A.ws_ml, A.out, A.Hq, A.G);
+    return (int)hipGetLastError();
+}
+
+int launch_attention(const tc_plan *p, const tc_kv_pool *pool, const void *q, void *out, float scale, void *workspace,
+                     void *stream) {
+    AttnArgs A;
+    A.k_pool = (const uint16_t *)pool->k_pool;
+    A.v_pool = (const uint16_t *)pool->v_pool;
+    A.q = (const uint16_t *)q;
+    A.out = (uint16_t *)out;
+    A.pages = p->dev + p->off_pages;
+    A.prefill = p->dev + p->off_prefill;
+    A.decode = p->dev + p->off_decode;
+    A.ws_o = (float *)workspace;
+    A.ws_ml = A.ws_o ? A.ws_o + (size_t)p->n_partials * p->G * p->D : nullptr;
+    A.n_prefill = p->n_prefill;
+    A.n_decode = p->n_decode;
+    A.Hq = p->Hq;
+    A.Hkv = p->Hkv;
+    A.G = p->G;
+    A.scale_log2 = scale * 1.4426950408889634f;
+    return p->D == 128 ? launch_attention_d<128>(p, A, (hipStream_t)stream) : launch_attention_d<64>(p, A, (hipStream_t)stream);
+}
+
+}  // namespace tc

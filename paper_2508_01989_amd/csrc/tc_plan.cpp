@@ -1,0 +1,253 @@
+// Host-side planner: turns one mixed batch (a prefill chunk at its chunk offset plus
+// piggybacked decodes, paper Sec. 2.2 / 3.2) into the integer work list the fused
+// attention kernel consumes.  Runs once per iteration; every layer reuses the plan.
+#include <algorithm>
+#include <cstring>
+#include <new>
+
+#include "tc_internal.h"
+
+namespace tc {
+
+static thread_local std::string g_last_error;
+
+void set_error(const std::string &msg) { g_last_error = msg; }
+
+static tc_status fail(tc_status s, const std::string &msg) {
+    set_error(msg);
+    return s;
+}
+
+tc_status check_pool_matches(const tc_plan *plan, const tc_kv_pool *pool, bool need_ptrs) {
+    if (!plan || !pool) return fail(TC_ERR_NULL, "plan or pool is NULL");
+    if (pool->num_q_heads != plan->Hq || pool->num_kv_heads != plan->Hkv || pool->head_dim != plan->D ||
+        pool->block_size != kBlock || pool->num_blocks != plan->num_blocks || pool->dtype != TC_BF16)
+        return fail(TC_ERR_SHAPE, "pool shape differs from the shape the plan was built for");
+    if (need_ptrs && (!pool->k_pool || !pool->v_pool)) return fail(TC_ERR_NULL, "k_pool or v_pool is NULL");
+    return TC_OK;
+}
+
+// Decode KV ranges are cut into equal splits so that work items are uniform; the split
+// is the largest of 1024..128 tokens that still yields enough items to fill the chip.
+static int choose_split(int64_t decode_token_heads) {
+    const int64_t want_items = 4 * 256 * kWgWaves;  // a few wavefronts of work per wave slot
+    for (int split = kMaxSplitPages * kBlock; split > 128; split /= 2)
+        if (decode_token_heads / split >= want_items) return split;
+    return 128;
+}
+
+tc_status build_plan(const tc_kv_pool *pool, const tc_batch *b, tc_plan **out) {
+    if (!pool || !b || !out) return fail(TC_ERR_NULL, "pool, batch or out is NULL");
+    *out = nullptr;
+    const int Hq = pool->num_q_heads, Hkv = pool->num_kv_heads, D = pool->head_dim;
+    if (pool->dtype != TC_BF16) return fail(TC_ERR_SHAPE, "dtype must be TC_BF16");
+    if (pool->block_size != kBlock) return fail(TC_ERR_SHAPE, "block_size must be 16");
+    if (D != 64 && D != 128) return fail(TC_ERR_SHAPE, "head_dim must be 64 or 128");
+    if (Hkv <= 0 || Hq <= 0 || Hq % Hkv) return fail(TC_ERR_SHAPE, "num_q_heads must be a positive multiple of num_kv_heads");
+    const int G = Hq / Hkv;
+    if (G > 16) return fail(TC_ERR_SHAPE, "more than 16 query heads per KV head is not supported");
+    if (pool->num_blocks <= 0 || pool->num_blocks * kBlock >= (int64_t)1 << 31)
+        return fail(TC_ERR_SHAPE, "num_blocks must be in [1, 2^27)");
+    if (b->num_seqs < 0) return fail(TC_ERR_SPAN, "negative num_seqs");
+    const int S = b->num_seqs;
+    if (S > 0 && (!b->q_start || !b->ctx_len || !b->block_table)) return fail(TC_ERR_NULL, "a batch array is NULL");
+    if (S > 0 && b->max_blocks <= 0) return fail(TC_ERR_BLOCK, "max_blocks must be positive");
+    if (S > 0 && b->q_start[0] != 0) return fail(TC_ERR_SPAN, "q_start[0] must be 0");
+
+    tc_plan *p = new (std::nothrow) tc_plan();
+    if (!p) return fail(TC_ERR_DEVICE, "out of host memory");
+    p->Hq = Hq; p->Hkv = Hkv; p->D = D; p->G = G; p->num_blocks = pool->num_blocks; p->S = S;
+    p->q_start.assign(S + 1, 0);
+    p->ctx_len.assign(S, 0);
+    p->page_off.assign(S + 1, 0);
+
+    int64_t pages = 0, decode_tokens = 0;
+    for (int s = 0; s < S; s++) {
+        const int64_t a = b->q_start[s], e = b->q_start[s + 1], ctx = b->ctx_len[s];
+        if (e <= a) { delete p; return fail(TC_ERR_SPAN, "q_start must be strictly increasing (every sequence needs a query token)"); }
+        if (ctx < 0) { delete p; return fail(TC_ERR_SPAN, "negative ctx_len"); }
+        const int64_t kv = ctx + (e - a);
+        if (kv >= ((int64_t)1 << 31) - 64) { delete p; return fail(TC_ERR_SPAN, "ctx_len + q_len too large"); }
+        const int64_t np = (kv + kBlock - 1) / kBlock;
+        if (np > b->max_blocks) { delete p; return fail(TC_ERR_BLOCK, "max_blocks smaller than the pages a sequence needs"); }
+        p->q_start[s + 1] = (int32_t)e;
+        p->ctx_len[s] = (int32_t)ctx;
+        pages += np;
+        if (pages >= ((int64_t)1 << 31)) { delete p; return fail(TC_ERR_BLOCK, "too many pages in one batch"); }
+        p->page_off[s + 1] = (int32_t)pages;
+        if (e - a == 1) { p->n_decode_seqs++; decode_tokens += kv; } else p->n_prefill_seqs++;
+    }
+    p->T = S ? p->q_start[S] : 0;
+    p->total_pages = pages;
+    p->split_tokens = choose_split(decode_tokens * Hkv);
+
+    // ---- section sizes
+    const int pos_per_item = kPrefillRows / G;
+    int64_t n_prefill = 0, n_decode = 0, n_merge = 0, n_partials = 0;
+    for (int s = 0; s < S; s++) {
+        const int q = p->q_start[s + 1] - p->q_start[s];
+        if (q > 1) n_prefill += (int64_t)((q + pos_per_item - 1) / pos_per_item) * Hkv;
+        else {
+            const int64_t kv = (int64_t)p->ctx_len[s] + 1;
+            const int64_t ns = (kv + p->split_tokens - 1) / p->split_tokens;
+            n_decode += ns * Hkv;
+            if (ns > 1) { n_merge += Hkv; n_partials += ns * Hkv; }
+        }
+    }
+    if (n_prefill + n_decode >= ((int64_t)1 << 28)) { delete p; return fail(TC_ERR_SPAN, "batch too large"); }
+    p->n_prefill = (int)n_prefill; p->n_decode = (int)n_decode; p->n_merge = (int)n_merge; p->n_partials = (int)n_partials;
+
+    p->off_slot = 0;
+    p->off_pages = p->off_slot + (size_t)p->T;
+    p->off_prefill = p->off_pages + (size_t)pages;
+    p->off_decode = p->off_prefill + (size_t)n_prefill * kItemInts;
+    p->off_merge = p->off_decode + (size_t)n_decode * kItemInts;
+    const size_t total = p->off_merge + (size_t)n_merge * kItemInts;
+    p->host.assign(std::max<size_t>(total, 1), 0);
+    int32_t *H = p->host.data();
+
+    // ---- pages (validated) and append slots
+    for (int s = 0; s < S; s++) {
+        const int32_t *row = b->block_table + (int64_t)s * b->max_blocks;
+        const int np = p->page_off[s + 1] - p->page_off[s];
+        int32_t *dst = H + p->off_pages + p->page_off[s];
+        for (int i = 0; i < np; i++) {
+            if (row[i] < 0 || row[i] >= pool->num_blocks) { delete p; return fail(TC_ERR_BLOCK, "block table entry outside the pool"); }
+            dst[i] = row[i];
+        }
+        const int q = p->q_start[s + 1] - p->q_start[s];
+        for (int i = 0; i < q; i++) {
+            const int64_t pos = (int64_t)p->ctx_len[s] + i;
+            H[p->off_slot + p->q_start[s] + i] = (int32_t)((int64_t)dst[pos / kBlock] * kBlock + pos % kBlock);
+        }
+    }
+
+    // ---- prefill items: heaviest (latest positions, longest KV range) first; KV head is the
+    // fastest index so that workgroup id % Hkv names the KV head (one L2 per 8th workgroup).
+    struct Tile { int seq, pos0, npos; int64_t cost; };
+    std::vector<Tile> tiles;
+    for (int s = 0; s < S; s++) {
+        const int q = p->q_start[s + 1] - p->q_start[s];
+        if (q <= 1) continue;
+        for (int pos0 = 0; pos0 < q; pos0 += pos_per_item) {
+            const int npos = std::min(pos_per_item, q - pos0);
+            tiles.push_back({s, pos0, npos, (int64_t)p->ctx_len[s] + pos0 + npos});
+        }
+    }
+    std::stable_sort(tiles.begin(), tiles.end(), [](const Tile &x, const Tile &y) { return x.cost > y.cost; });
+    int32_t *pf = H + p->off_prefill;
+    for (const Tile &t : tiles)
+        for (int h = 0; h < Hkv; h++, pf += kItemInts) {
+            pf[PF_SEQ] = t.seq; pf[PF_KVH] = h; pf[PF_POS0] = t.pos0; pf[PF_NPOS] = t.npos;
+            pf[PF_QROW0] = p->q_start[t.seq]; pf[PF_CTX] = p->ctx_len[t.seq];
+            pf[PF_PAGEOFF] = p->page_off[t.seq]; pf[PF_NPAGES] = p->page_off[t.seq + 1] - p->page_off[t.seq];
+        }
+
+    // ---- decode items: longest splits first so the tail of the launch is short work.
+    struct Split { int seq, begin, end, idx, nsplit; };
+    std::vector<Split> splits;
+    std::vector<int32_t> slot0(S, -1);
+    int32_t next_slot = 0;
+    int32_t *mg = H + p->off_merge;
+    for (int s = 0; s < S; s++) {
+        if (p->q_start[s + 1] - p->q_start[s] != 1) continue;
+        const int kv = p->ctx_len[s] + 1;
+        const int ns = (kv + p->split_tokens - 1) / p->split_tokens;
+        if (ns > 1) {
+            slot0[s] = next_slot;
+            for (int h = 0; h < Hkv; h++, mg += kItemInts) {
+                mg[MG_SEQ] = s; mg[MG_KVH] = h; mg[MG_QROW] = p->q_start[s];
+                mg[MG_SLOT0] = next_slot + h * ns; mg[MG_NSPLIT] = ns;
+            }
+            next_slot += ns * Hkv;
+        }
+        for (int i = 0; i < ns; i++)
+            splits.push_back({s, i * p->split_tokens, std::min(kv, (i + 1) * p->split_tokens), i, ns});
+    }
+    std::stable_sort(splits.begin(), splits.end(),
+                     [](const Split &x, const Split &y) { return x.end - x.begin > y.end - y.begin; });
+    int32_t *dc = H + p->off_decode;
+    for (const Split &sp : splits)
+        for (int h = 0; h < Hkv; h++, dc += kItemInts) {
+            dc[DC_SEQ] = sp.seq; dc[DC_KVH] = h; dc[DC_BEGIN] = sp.begin; dc[DC_END] = sp.end;
+            dc[DC_QROW] = p->q_start[sp.seq];
+            dc[DC_SLOT] = sp.nsplit > 1 ? slot0[sp.seq] + h * sp.nsplit + sp.idx : -1;
+            dc[DC_PAGEOFF] = p->page_off[sp.seq];
+        }
+    *out = p;
+    return TC_OK;
+}
+
+}  // namespace tc
+
+extern "C" {
+
+tc_status tc_plan_create_host(const tc_kv_pool *pool, const tc_batch *batch, tc_plan **out) {
+    return tc::build_plan(pool, batch, out);
+}
+
+tc_status tc_plan_create(const tc_kv_pool *pool, const tc_batch *batch, void *stream, tc_plan **out) {
+    tc_status st = tc::build_plan(pool, batch, out);
+    if (st != TC_OK) return st;
+    int err = tc::upload_plan(*out, stream);
+    if (err) {
+        tc::set_error(std::string("plan upload failed: ") + tc::hip_error_text(err));
+        tc_plan_destroy(*out);
+        *out = nullptr;
+        return TC_ERR_DEVICE;
+    }
+    return TC_OK;
+}
+
+tc_status tc_plan_get_info(const tc_plan *p, tc_plan_info *info) {
+    if (!p || !info) { tc::set_error("plan or info is NULL"); return TC_ERR_NULL; }
+    std::memset(info, 0, sizeof *info);
+    info->num_seqs = p->S; info->total_q = p->T;
+    info->num_prefill_seqs = p->n_prefill_seqs; info->num_decode_seqs = p->n_decode_seqs;
+    info->num_prefill_items = p->n_prefill; info->num_decode_items = p->n_decode;
+    info->num_merge_items = p->n_merge; info->num_partials = p->n_partials;
+    info->split_tokens = p->split_tokens; info->rows_per_prefill_item = tc::kPrefillRows;
+    info->grid_blocks = p->grid_blocks(); info->block_threads = tc::kWgThreads;
+    info->total_pages = p->total_pages;
+    return TC_OK;
+}
+
+tc_status tc_plan_copy_items(const tc_plan *p, int32_t kind, int32_t *dst, size_t cap_items) {
+    if (!p || !dst) { tc::set_error("plan or dst is NULL"); return TC_ERR_NULL; }
+    size_t off, n;
+    if (kind == 0) { off = p->off_prefill; n = p->n_prefill; }
+    else if (kind == 1) { off = p->off_decode; n = p->n_decode; }
+    else if (kind == 2) { off = p->off_merge; n = p->n_merge; }
+    else { tc::set_error("kind must be 0, 1 or 2"); return TC_ERR_ARG; }
+    n = std::min(n, cap_items);
+    std::memcpy(dst, p->host.data() + off, n * tc::kItemInts * sizeof(int32_t));
+    return TC_OK;
+}
+
+size_t tc_plan_workspace_bytes(const tc_plan *p) { return p ? p->workspace_bytes() : 0; }
+
+void tc_plan_destroy(tc_plan *p) {
+    if (!p) return;
+    tc::free_plan_device(p);
+    delete p;
+}
+
+const char *tc_status_str(tc_status s) {
+    switch (s) {
+        case TC_OK: return "TC_OK";
+        case TC_ERR_NULL: return "TC_ERR_NULL";
+        case TC_ERR_SHAPE: return "TC_ERR_SHAPE";
+        case TC_ERR_SPAN: return "TC_ERR_SPAN";
+        case TC_ERR_BLOCK: return "TC_ERR_BLOCK";
+        case TC_ERR_WORKSPACE: return "TC_ERR_WORKSPACE";
+        case TC_ERR_DEVICE: return "TC_ERR_DEVICE";
+        case TC_ERR_ARG: return "TC_ERR_ARG";
+    }
+    return "TC_ERR_UNKNOWN";
+}
+
+const char *tc_last_error(void) { return tc::g_last_error.c_str(); }
+
+int32_t tc_version(void) { return 1; }
+
+}  // extern "C"
