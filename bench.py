@@ -1,0 +1,142 @@
+#!/usr/bin/env python3
+"""Bench of the mixed-batch paged-attention hot path on one MI355X.
+
+A step = one pass of the whole path for one layer over one synthetic mixed batch that is
+already resident in HBM: tc_kv_append of the iteration's tokens, then tc_mixed_attention
+(one fused launch for the prefill chunk and the piggybacked decodes, plus the split merge).
+The plan is built once per batch (once per iteration in a serving loop, shared by all
+layers) and its time is reported separately.  Prints ONE JSON line.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA
+PEAK_HBM_GBS = 8000.0       # MI355X HBM3E
+WORKLOADS = ["tiny", "prefill_heavy", "decode_heavy", "pure_decode", "long_prompt"]
+
+
+def cpu_baseline(batch, work, budget_rows=96):
+    """Time the fp64 oracle, as it stands, on a bounded sample of the same batch: the KV
+    append of the iteration plus attention for a stratified sample of query rows; scale by
+    (query,key) pairs to a whole-batch rate."""
+    import oracle
+    sp = batch.spec
+    k_pool, v_pool = oracle.new_pool(batch.num_blocks, sp.num_kv_heads, sp.head_dim, sp.block_size)
+    keep = np.flatnonzero(sp.ctx_len > 0)
+    if len(keep):
+        oracle.kv_append(k_pool, v_pool, sp.num_kv_heads, sp.head_dim, sp.block_size, batch.hist_start.astype(np.int32),
+                         np.zeros(sp.num_seqs, np.int32), batch.block_table, batch.k_hist, batch.v_hist)
+    T = batch.total_q
+    rows = np.unique(np.linspace(0, T - 1, min(budget_rows, T)).round().astype(np.int32))
+    t0 = time.perf_counter()
+    oracle.kv_append(k_pool, v_pool, sp.num_kv_heads, sp.head_dim, sp.block_size, batch.q_start, sp.ctx_len,
+                     batch.block_table, batch.k_new, batch.v_new)
+    t_append = time.perf_counter() - t0
+    t0 = time.perf_counter()
+    oracle.attention(k_pool, v_pool, sp.num_q_heads, sp.num_kv_heads, sp.head_dim, sp.block_size, batch.q_start,
+                     sp.ctx_len, batch.block_table, batch.q, sp.scale, rows)
+    t_attn = time.perf_counter() - t0
+    owner = np.repeat(np.arange(sp.num_seqs), sp.q_len)
+    pos = sp.ctx_len[owner] + (np.arange(T) - batch.q_start[owner])
+    pairs_sample = int((pos[rows].astype(np.int64) + 1).sum())
+    est = t_append + t_attn * work["pairs_per_head"] / pairs_sample
+    return {"value": T / est, "unit": "tokens/s", "cores": oracle.num_threads(), "kind": "oracle",
+            "sample": f"fp64 oracle: KV append of all {T} rows ({t_append:.3f} s) + attention of {len(rows)} evenly spaced "
+                      f"query rows, all heads ({t_attn:.2f} s, {pairs_sample} of {work['pairs_per_head']} (q,k) pairs per head); "
+                      f"time scaled by pairs to the whole batch ({est:.1f} s)"}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--workload", default="prefill_heavy", choices=WORKLOADS)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build runs on one GPU only (independent instances shard by data, "
+              "tensor parallelism by KV head; neither is built). Use --gpus 1.", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    import workloads as W
+    import paper_2508_01989_amd as tc
+    from paper_2508_01989_amd.harness import DeviceBatch
+
+    tc.lib()  # fails loudly if the HIP library is not built
+    idx = WORKLOADS.index(args.workload)
+    spec = W.config_spec(idx)
+    batch = W.make_batch(spec)
+    work = W.algorithmic_work(spec)
+    torch.cuda.set_device(0)
+    stream = torch.cuda.Stream()
+    with torch.cuda.stream(stream):
+        db = DeviceBatch(batch, stream=stream)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(5):
+            p = tc.Plan(db.pool, batch.q_start, spec.ctx_len, batch.block_table, stream=stream)
+            torch.cuda.synchronize()
+            p.destroy()
+        plan_ms = (time.perf_counter() - t0) / 5 * 1e3
+
+        for _ in range(args.warmup):
+            db.step()
+        ev = [[torch.cuda.Event(enable_timing=True) for _ in range(3)] for _ in range(args.steps)]
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for i in range(args.steps):
+            ev[i][0].record(stream)
+            db.append()
+            ev[i][1].record(stream)
+            db.attention()
+            ev[i][2].record(stream)
+        torch.cuda.synchronize()
+        wall = time.perf_counter() - t0
+    append_ms = float(np.mean([e[0].elapsed_time(e[1]) for e in ev]))
+    attn_ms = float(np.mean([e[1].elapsed_time(e[2]) for e in ev]))
+    ms_per_step = wall / args.steps * 1e3
+    T = work["tokens"]
+
+    prefill_bound = work["flops"] / (PEAK_BF16_TFLOPS * 1e12) >= work["bytes"] / (PEAK_HBM_GBS * 1e9)
+    if prefill_bound:
+        achieved = work["flops"] / (attn_ms * 1e-3) / 1e12
+        roofline = {"bound": "mfma", "achieved": achieved, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
+                    "frac": achieved / PEAK_BF16_TFLOPS, "traffic": None}
+    else:
+        attn_bytes = work["kv_bytes_prefill"] + work["kv_bytes_decode"] + work["qo_bytes"]
+        achieved = attn_bytes / (attn_ms * 1e-3) / 1e9
+        roofline = {"bound": "hbm", "achieved": achieved, "peak": PEAK_HBM_GBS, "unit": "GB/s",
+                    "frac": achieved / PEAK_HBM_GBS, "traffic": None}
+    roofline.update({"kernel": "mixed_attention_kernel (+ split_merge_kernel)", "kernel_ms": attn_ms,
+                     "algorithmic_flops": work["flops"], "algorithmic_bytes": work["bytes"]})
+
+    line = {"metric": "mixed_batch_attention_tokens_per_s", "value": T / (ms_per_step * 1e-3), "unit": "tokens/s",
+            "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
+            "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+            "config": {"workload": args.workload, "num_q_heads": spec.num_q_heads, "num_kv_heads": spec.num_kv_heads,
+                       "head_dim": spec.head_dim, "block_size": spec.block_size, "num_seqs": spec.num_seqs,
+                       "tokens": T, "prefill_chunk": int(spec.q_len.max()) if (spec.q_len > 1).any() else 0,
+                       "sum_kv_len": work["sum_kv_len"], "seed": spec.seed},
+            "append_ms": append_ms, "attention_ms": attn_ms, "plan_ms": plan_ms,
+            "hbm_frac_of_step": work["bytes"] / (ms_per_step * 1e-3) / 1e9 / PEAK_HBM_GBS,
+            "mfma_frac_of_step": work["flops"] / (ms_per_step * 1e-3) / 1e12 / PEAK_BF16_TFLOPS,
+            "roofline": roofline}
+    if not args.no_cpu_baseline:
+        line["cpu_baseline"] = cpu_baseline(batch, work)
+    print(json.dumps(line))
+
+
+if __name__ == "__main__":
+    main()

@@ -1,0 +1,149 @@
+"""Host-side checks of the C ABI that need no GPU: the library loads and exports every
+symbol include/tc.h declares, descriptor validation returns the documented status codes,
+and the planner's work list covers the batch exactly."""
+import ctypes as C
+import os
+import re
+
+import numpy as np
+import pytest
+
+import workloads as W
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def tc():
+    import paper_2508_01989_amd as tc
+    if not os.path.exists(tc.LIB_PATH):
+        from paper_2508_01989_amd.build import build
+        build()
+    tc.lib()
+    return tc
+
+
+def test_header_compiles_as_c99(tmp_path):
+    src = tmp_path / "t.c"
+    src.write_text('#include "tc.h"\nint main(void){ tc_plan_info i; (void)i; return TC_OK; }\n')
+    rc = os.system(f"gcc -std=c99 -Wall -Werror -pedantic -I {ROOT}/include -c {src} -o {tmp_path}/t.o")
+    assert rc == 0
+
+
+def test_library_exports_every_declared_symbol(tc):
+    header = open(os.path.join(ROOT, "include", "tc.h")).read()
+    header = re.sub(r"/\*.*?\*/", "", header, flags=re.S)
+    declared = set(re.findall(r"\b(tc_[a-z_]+)\s*\(", header))
+    assert declared == set(tc.EXPORTS)
+    L = C.CDLL(tc.LIB_PATH)
+    for name in declared:
+        assert hasattr(L, name), name
+    assert tc.tc_version() >= 1
+    assert tc.status_str(tc.TC_ERR_BLOCK) == "TC_ERR_BLOCK"
+
+
+def _plan(tc, Hq=8, Hkv=2, D=128, q_len=(5, 1), ctx=(3, 40), nb=32, table=None, **kw):
+    sp = W.custom_spec("x", Hq, Hkv, D, q_len, ctx)
+    if table is None:
+        table, mb, _ = W.make_tables(W.custom_spec("x", Hq, Hkv, D, q_len, ctx, num_blocks=nb), np.random.default_rng(0))
+    qs = np.zeros(len(q_len) + 1, np.int32)
+    qs[1:] = np.cumsum(q_len)
+    pool = tc.make_pool(Hq, Hkv, D, nb, **kw)
+    return tc.Plan(pool, qs, np.asarray(ctx, np.int32), table, host_only=True)
+
+
+def _status(tc, fn):
+    with pytest.raises(tc.TcError) as e:
+        fn()
+    assert tc.last_error() != ""
+    return e.value.status
+
+
+def test_validation_status_codes(tc):
+    assert _status(tc, lambda: _plan(tc, D=96)) == tc.TC_ERR_SHAPE
+    assert _status(tc, lambda: _plan(tc, Hq=7, Hkv=2)) == tc.TC_ERR_SHAPE
+    assert _status(tc, lambda: _plan(tc, Hq=34, Hkv=2)) == tc.TC_ERR_SHAPE       # G = 17
+    assert _status(tc, lambda: _plan(tc, block_size=32)) == tc.TC_ERR_SHAPE
+    assert _status(tc, lambda: _plan(tc, dtype=0)) == tc.TC_ERR_SHAPE
+    assert _status(tc, lambda: _plan(tc, ctx=(-1, 40))) == tc.TC_ERR_SPAN
+    good = _plan(tc)
+    assert good.info.num_seqs == 2
+    table = np.zeros((2, 3), np.int32)
+    assert _status(tc, lambda: _plan(tc, table=np.zeros((2, 2), np.int32))) == tc.TC_ERR_BLOCK   # 41 tokens need 3 pages
+    bad = table.copy(); bad[1, 2] = 32
+    assert _status(tc, lambda: _plan(tc, table=bad)) == tc.TC_ERR_BLOCK
+    bad = table.copy(); bad[0, 0] = -1
+    assert _status(tc, lambda: _plan(tc, table=bad)) == tc.TC_ERR_BLOCK
+    # entries past the used prefix are never looked at
+    ok = np.full((2, 9), W.TABLE_SENTINEL, np.int32); ok[0, :1] = 1; ok[1, :3] = [2, 3, 4]
+    assert _plan(tc, table=ok).info.total_pages == 4
+    # spans: zero-length sequence, q_start[0] != 0
+    pool = tc.make_pool(8, 2, 128, 32)
+    z = np.zeros(2, np.int32)
+    assert _status(tc, lambda: tc.Plan(pool, np.array([0, 2, 2], np.int32), z, table, host_only=True)) == tc.TC_ERR_SPAN
+    assert _status(tc, lambda: tc.Plan(pool, np.array([1, 2, 3], np.int32), z, table, host_only=True)) == tc.TC_ERR_SPAN
+    # NULL arguments
+    L = tc.lib()
+    h = C.c_void_p()
+    assert L.tc_plan_create_host(None, None, C.byref(h)) == tc.TC_ERR_NULL
+    assert L.tc_plan_get_info(None, None) == tc.TC_ERR_NULL
+    assert L.tc_plan_workspace_bytes(None) == 0
+    L.tc_plan_destroy(None)
+
+
+def test_host_only_plan_cannot_be_launched(tc):
+    p = _plan(tc)
+    pool = tc.make_pool(8, 2, 128, 32, k_pool=4096, v_pool=4096)
+    assert _status(tc, lambda: tc.tc_kv_append(p, pool, 4096, 4096)) == tc.TC_ERR_ARG
+    pool2 = tc.make_pool(8, 2, 128, 33, k_pool=4096, v_pool=4096)
+    assert _status(tc, lambda: tc.tc_kv_append(p, pool2, 4096, 4096)) == tc.TC_ERR_SHAPE
+    pool3 = tc.make_pool(8, 2, 128, 32)
+    assert _status(tc, lambda: tc.tc_kv_append(p, pool3, 4096, 4096)) == tc.TC_ERR_NULL
+
+
+def test_empty_batch_is_a_valid_plan(tc):
+    pool = tc.make_pool(8, 2, 128, 4)
+    p = tc.Plan(pool, np.zeros(1, np.int32), np.zeros(0, np.int32), np.zeros((0, 1), np.int32), host_only=True)
+    assert p.info.grid_blocks == 0 and p.workspace_bytes == 0
+
+
+@pytest.mark.parametrize("idx", [0, 1, 2, 3, 4])
+def test_work_list_covers_the_batch_exactly(tc, idx):
+    sp = W.config_spec(idx)
+    table, mb, nb = W.make_tables(sp, np.random.default_rng(3))
+    qs = np.zeros(sp.num_seqs + 1, np.int32)
+    qs[1:] = np.cumsum(sp.q_len)
+    pool = tc.make_pool(sp.num_q_heads, sp.num_kv_heads, sp.head_dim, nb)
+    p = tc.Plan(pool, qs, sp.ctx_len, table, host_only=True)
+    info, G, Hkv = p.info, sp.num_q_heads // sp.num_kv_heads, sp.num_kv_heads
+    pf, dc, mg = p.items(0), p.items(1), p.items(2)
+    # prefill: every (sequence, KV head) has its positions covered once, in tiles of <= 256/G positions
+    for s in np.flatnonzero(sp.q_len > 1):
+        for h in range(Hkv):
+            it = pf[(pf[:, 0] == s) & (pf[:, 1] == h)]
+            it = it[np.argsort(it[:, 2])]
+            assert it[0, 2] == 0 and np.all(it[1:, 2] == it[:-1, 2] + it[:-1, 3])
+            assert it[-1, 2] + it[-1, 3] == sp.q_len[s] and np.all(it[:, 3] * G <= info.rows_per_prefill_item)
+            assert np.all(it[:, 4] == qs[s]) and np.all(it[:, 5] == sp.ctx_len[s])
+            assert np.all(it[:, 7] == (sp.kv_len[s] + 15) // 16)
+    assert len(pf) == sum(-(-int(q) // (256 // G)) for q in sp.q_len[sp.q_len > 1]) * Hkv
+    # heaviest prefill tiles first; KV head is the fastest index
+    cost = pf[:, 5] + pf[:, 2] + pf[:, 3]
+    assert np.all(np.diff(cost[::Hkv]) <= 0) and np.all(pf[:, 1] == np.arange(len(pf)) % Hkv)
+    # decode: splits tile [0, kv_len) page-aligned, <= 64 pages each, slots unique and dense
+    slots = []
+    for s in np.flatnonzero(sp.q_len == 1):
+        it = dc[(dc[:, 0] == s) & (dc[:, 1] == 0)]
+        it = it[np.argsort(it[:, 2])]
+        assert it[0, 2] == 0 and np.all(it[1:, 2] == it[:-1, 3]) and it[-1, 3] == sp.kv_len[s]
+        assert np.all(it[:, 2] % 16 == 0) and np.all(it[:, 3] - it[:, 2] <= 1024)
+        assert np.all((it[:, 5] >= 0) == (len(it) > 1))
+    used = dc[dc[:, 5] >= 0, 5]
+    assert len(used) == info.num_partials and sorted(used.tolist()) == list(range(info.num_partials))
+    assert np.all(np.diff((dc[:, 3] - dc[:, 2])[::Hkv]) <= 0)
+    # merge items name exactly the slots of their splits
+    for m in mg:
+        mine = dc[(dc[:, 0] == m[0]) & (dc[:, 1] == m[1])]
+        assert sorted(mine[:, 5].tolist()) == list(range(m[3], m[3] + m[4]))
+    assert p.workspace_bytes == info.num_partials * G * (sp.head_dim + 2) * 4
+    assert info.grid_blocks == info.num_prefill_items + -(-info.num_decode_items // 8)

@@ -1,0 +1,211 @@
+"""GPU parity: the HIP path, called through the C ABI, against the fp64 CPU oracle on the
+same seeded inputs.  KV append and gather must be bit-exact; attention outputs must satisfy
+max|gpu - ref| <= 1e-2 and ||gpu - ref||_2 / ||ref||_2 <= 5e-3 (the stated tolerance of this
+build; per-sequence rel-L2 is also bounded, more loosely, so a broken short sequence cannot
+hide in the global norm)."""
+import zlib
+
+import numpy as np
+import pytest
+
+import oracle
+import workloads as W
+
+pytestmark = pytest.mark.gpu
+
+MAX_ABS, REL_L2 = 1e-2, 5e-3
+
+
+@pytest.fixture(scope="module")
+def H():
+    import torch
+    assert torch.cuda.is_available(), "these tests need the MI355X"
+    import paper_2508_01989_amd.harness as harness
+    return harness
+
+
+def check_attention(got, ref, batch, rows=None, tag=""):
+    assert np.isfinite(got).all(), f"{tag}: non-finite output"
+    err = np.abs(got - ref)
+    rel = np.linalg.norm(got - ref) / np.linalg.norm(ref)
+    assert err.max() <= MAX_ABS, f"{tag}: max abs {err.max()}"
+    assert rel <= REL_L2, f"{tag}: rel-L2 {rel}"
+    if rows is None:
+        for s in range(batch.spec.num_seqs):
+            a, b = int(batch.q_start[s]), int(batch.q_start[s + 1])
+            r = np.linalg.norm(got[a:b] - ref[a:b]) / max(np.linalg.norm(ref[a:b]), 1e-30)
+            assert r <= 2 * REL_L2, f"{tag}: sequence {s} rel-L2 {r}"
+    return err.max(), rel
+
+
+def run_and_compare(H, batch, tag, rows=None):
+    print(f"[case] {tag}: S={batch.spec.num_seqs} T={batch.total_q} Hq={batch.spec.num_q_heads} "
+          f"Hkv={batch.spec.num_kv_heads} D={batch.spec.head_dim} seed={batch.spec.seed}", flush=True)
+    ref, kp, vp = oracle.run_batch(batch, rows=rows)
+    db = H.DeviceBatch(batch)
+    db.step()
+    got = db.out_f64()
+    gk, gv = db.pools_host()
+    assert np.array_equal(gk, kp), f"{tag}: K pool differs from the oracle's"
+    assert np.array_equal(gv, vp), f"{tag}: V pool differs from the oracle's"
+    if rows is not None:
+        got = got[rows]
+    return check_attention(got, ref, batch, rows, tag), db
+
+
+SMALL = {
+    # name: (Hq, Hkv, D, q_len, ctx)
+    "decode_single_token_context": (4, 1, 128, [1], [0]),
+    "decode_page_boundaries": (8, 2, 128, [1, 1, 1, 1, 1], [14, 15, 16, 31, 32]),
+    "decode_split_boundaries": (8, 2, 128, [1, 1, 1, 1], [126, 127, 128, 255]),
+    "decode_long_ragged": (32, 8, 128, [1, 1, 1], [3000, 1025, 777]),
+    "prefill_two_rows": (4, 1, 128, [2], [0]),
+    "prefill_ragged_tiles": (8, 2, 128, [77], [0]),
+    "prefill_offset_not_page_aligned": (8, 2, 128, [130], [37]),
+    "prefill_offset_tile_aligned": (32, 8, 128, [128], [256]),
+    "two_prefill_segments_and_decodes": (8, 2, 128, [40, 1, 70, 1], [5, 99, 300, 0]),
+    "mha_g1": (4, 4, 128, [300, 1], [20, 200]),
+    "gqa_g2": (4, 2, 128, [150, 1], [11, 140]),
+    "gqa_g8": (16, 2, 128, [90, 1, 1], [64, 513, 30]),
+    "gqa_g16": (16, 1, 128, [33, 1], [3, 100]),
+    "gqa_g3": (6, 2, 128, [100, 1], [28, 75]),
+    "gqa_g5": (10, 2, 128, [120, 1], [0, 260]),
+    "head_dim_64": (8, 8, 64, [64, 1, 1, 1, 1], [0, 36, 63, 99, 127]),
+    "head_dim_64_gqa": (8, 2, 64, [200, 1, 1], [45, 1000, 17]),
+}
+
+
+@pytest.mark.parametrize("name", list(SMALL))
+def test_small_cases_match_oracle(H, name):
+    Hq, Hkv, D, q_len, ctx = SMALL[name]
+    b = W.make_batch(W.custom_spec(name, Hq, Hkv, D, q_len, ctx, seed=zlib.crc32(name.encode()) % 10007))
+    run_and_compare(H, b, name)
+
+
+def test_config0_tiny_full(H):
+    b = W.make_batch(W.config_spec(0))
+    (mx, rel), db = run_and_compare(H, b, "config0 tiny")
+    for s in range(b.spec.num_seqs):
+        k, v = db.gather(s)
+        ke, ve = W.contiguous_kv(b, s)
+        assert np.array_equal(k, ke) and np.array_equal(v, ve)
+
+
+def stratified_rows(batch, every):
+    """All decode rows plus prefill rows {0, 1, 15, 16, 17, every `every`-th, last} of each chunk."""
+    rows = []
+    for s in range(batch.spec.num_seqs):
+        a, b = int(batch.q_start[s]), int(batch.q_start[s + 1])
+        if b - a == 1:
+            rows.append(a)
+        else:
+            pick = {0, 1, 15, 16, 17, b - a - 1} | set(range(0, b - a, every))
+            rows += [a + i for i in sorted(pick) if i < b - a]
+    return np.array(rows, np.int32)
+
+
+def test_config2_decode_heavy_full_size(H):
+    b = W.make_batch(W.config_spec(2))
+    run_and_compare(H, b, "config2 decode-heavy (full oracle)")
+
+
+def test_config1_prefill_heavy_full_size_sampled(H):
+    """The bench workload, in the launch configuration the bench times; the oracle checks a
+    stratified sample of rows (all decode rows, prefill rows across page and tile boundaries)."""
+    b = W.make_batch(W.config_spec(1))
+    rows = stratified_rows(b, 61)
+    run_and_compare(H, b, "config1 prefill-heavy (sampled rows)", rows=rows)
+
+
+def test_config3_pure_decode_full_size(H):
+    b = W.make_batch(W.config_spec(3))
+    run_and_compare(H, b, "config3 pure decode (full oracle)")
+
+
+def test_config4_long_prompt_full_size_sampled(H):
+    b = W.make_batch(W.config_spec(4))
+    rows = stratified_rows(b, 509)
+    run_and_compare(H, b, "config4 long prompt (sampled rows)", rows=rows)
+
+
+def test_bitwise_reproducible_and_independent_of_poison(H):
+    b = W.make_batch(W.custom_spec("repro", 32, 8, 128, [300, 1, 1, 1], [100, 2000, 50, 700], seed=77))
+    db = H.DeviceBatch(b)
+    db.step()
+    first = H.to_host(db.out).copy()
+    for _ in range(3):
+        db.out.fill_(0)
+        db.step()
+        assert np.array_equal(H.to_host(db.out), first)
+    # a different fill of the never-written pool slots must not change a single output bit
+    db2 = H.DeviceBatch(b, poison=0x7F80)  # +inf
+    db2.step()
+    assert np.array_equal(H.to_host(db2.out), first)
+
+
+def test_block_table_relabelling_is_bitwise_invisible(H):
+    b = W.make_batch(W.custom_spec("perm", 8, 2, 128, [100, 1, 1], [60, 300, 31], seed=5))
+    db = H.DeviceBatch(b)
+    db.step()
+    base = H.to_host(db.out).copy()
+    relabel = np.random.default_rng(4).permutation(b.num_blocks).astype(np.int32)
+    t2 = b.block_table.copy()
+    used = t2 != W.TABLE_SENTINEL
+    t2[used] = relabel[t2[used]]
+    b2 = W.Batch(b.spec, b.q_start, b.hist_start, t2, b.max_blocks, b.num_blocks, b.q, b.k_new, b.v_new, b.k_hist, b.v_hist)
+    db2 = H.DeviceBatch(b2)
+    db2.step()
+    assert np.array_equal(H.to_host(db2.out), base)
+
+
+def test_chunked_prefill_matches_one_shot_on_gpu(H):
+    """Feed one prompt as successive chunks through the library (append + attend per chunk, the way
+    an instance with a small chunk size would) and compare with the oracle's one-shot prefill."""
+    import paper_2508_01989_amd as tc
+    import torch
+    N, Hq, Hkv, D = 333, 8, 2, 128
+    one = W.make_batch(W.custom_spec("chunks", Hq, Hkv, D, [N], [0], seed=31))
+    ref, kp, vp = oracle.run_batch(one)
+    n = one.num_blocks * Hkv * 16 * D
+    k_pool = torch.full((n,), -1, dtype=torch.int16, device="cuda:0")
+    v_pool = torch.full((n,), -1, dtype=torch.int16, device="cuda:0")
+    pool = tc.make_pool(Hq, Hkv, D, one.num_blocks, k_pool, v_pool)
+    got = np.zeros_like(ref)
+    edges = [0, 1, 18, 82, 83, 211, N]
+    for a, c in zip(edges[:-1], edges[1:]):
+        plan = tc.Plan(pool, np.array([0, c - a], np.int32), np.array([a], np.int32), one.block_table)
+        q, kn, vn = (H.to_dev(x[a:c]) for x in (one.q, one.k_new, one.v_new))
+        out = torch.zeros((c - a, Hq, D), dtype=torch.int16, device="cuda:0")
+        ws = torch.empty(max(plan.workspace_bytes, 16), dtype=torch.uint8, device="cuda:0")
+        tc.tc_kv_append(plan, pool, kn, vn)
+        tc.tc_mixed_attention(plan, pool, q, out, one.spec.scale, ws, plan.workspace_bytes)
+        torch.cuda.synchronize()
+        u = H.to_host(out)
+        got[a:c] = (u.astype(np.uint32) << np.uint32(16)).view(np.float32).astype(np.float64)
+        plan.destroy()
+    assert np.array_equal(H.to_host(k_pool), kp) and np.array_equal(H.to_host(v_pool), vp)
+    check_attention(got, ref, one, tag="chunked prefill")
+
+
+def test_empty_batch_and_runtime_argument_errors(H):
+    import paper_2508_01989_amd as tc
+    import torch
+    b = W.make_batch(W.custom_spec("err", 8, 2, 128, [1, 1], [600, 20], seed=2))
+    db = H.DeviceBatch(b)
+    assert db.plan.workspace_bytes > 0
+    with pytest.raises(tc.TcError) as e:
+        tc.tc_mixed_attention(db.plan, db.pool, db.q, db.out, 0.1, db.workspace, db.plan.workspace_bytes - 1)
+    assert e.value.status == tc.TC_ERR_WORKSPACE
+    with pytest.raises(tc.TcError) as e:
+        tc.tc_mixed_attention(db.plan, db.pool, db.q, None, 0.1, db.workspace, db.plan.workspace_bytes)
+    assert e.value.status == tc.TC_ERR_NULL
+    with pytest.raises(tc.TcError) as e:
+        tc.tc_kv_gather(db.plan, db.pool, 2, db.q, db.q)
+    assert e.value.status == tc.TC_ERR_ARG
+    # an empty batch: every call is a no-op that returns TC_OK
+    empty = tc.Plan(db.pool, np.zeros(1, np.int32), np.zeros(0, np.int32), np.zeros((0, 1), np.int32))
+    before = H.to_host(db.k_pool).copy()
+    tc.tc_kv_append(empty, db.pool, None, None)
+    tc.tc_mixed_attention(empty, db.pool, None, None, 1.0)
+    torch.cuda.synchronize()
+    assert np.array_equal(H.to_host(db.k_pool), before)

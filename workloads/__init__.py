@@ -13,6 +13,8 @@ from __future__ import annotations
 
 from dataclasses import dataclass, field
 import math
+import os
+
 import numpy as np
 
 BASE_SEED = 0x7A1C41
@@ -156,15 +158,27 @@ def make_tables(spec: BatchSpec, rng) -> tuple[np.ndarray, int, int]:
     return table, max_blocks, num_blocks
 
 
-def _normal_bf16(rng, shape, value_scale, chunk=1 << 24) -> np.ndarray:
+def _normal_bf16(seed_key, shape, value_scale, chunk=1 << 22) -> np.ndarray:
+    """N(0,1) * value_scale rounded to bf16.  Every chunk of 2^22 values has its own generator
+    keyed by (seed_key, chunk index), so the result does not depend on the worker count."""
     n = int(np.prod(shape))
     out = np.empty(n, dtype=np.uint16)
-    for a in range(0, n, chunk):
-        b = min(n, a + chunk)
-        x = rng.standard_normal(b - a, dtype=np.float32)
+
+    def fill(ci):
+        a, b = ci * chunk, min(n, (ci + 1) * chunk)
+        x = np.random.default_rng([*seed_key, ci]).standard_normal(b - a, dtype=np.float32)
         if value_scale != 1.0:
             x *= np.float32(value_scale)
         out[a:b] = f32_to_bf16_bits(x)
+
+    n_chunks = (n + chunk - 1) // chunk
+    if n_chunks <= 1:
+        for ci in range(n_chunks):
+            fill(ci)
+    else:
+        from concurrent.futures import ThreadPoolExecutor
+        with ThreadPoolExecutor(max_workers=min(8, os.cpu_count() or 1)) as ex:
+            list(ex.map(fill, range(n_chunks)))
     return out.reshape(shape)
 
 
@@ -178,11 +192,11 @@ def make_batch(spec: BatchSpec) -> Batch:
     hist_start[1:] = np.cumsum(spec.ctx_len.astype(np.int64))
     T, Hs = int(q_start[-1]), int(hist_start[-1])
     Hq, Hkv, D = spec.num_q_heads, spec.num_kv_heads, spec.head_dim
-    q = _normal_bf16(rng, (T, Hq, D), spec.value_scale)
-    k_new = _normal_bf16(rng, (T, Hkv, D), spec.value_scale)
-    v_new = _normal_bf16(rng, (T, Hkv, D), spec.value_scale)
-    k_hist = _normal_bf16(rng, (Hs, Hkv, D), spec.value_scale)
-    v_hist = _normal_bf16(rng, (Hs, Hkv, D), spec.value_scale)
+    q = _normal_bf16((spec.seed, 1), (T, Hq, D), spec.value_scale)
+    k_new = _normal_bf16((spec.seed, 2), (T, Hkv, D), spec.value_scale)
+    v_new = _normal_bf16((spec.seed, 3), (T, Hkv, D), spec.value_scale)
+    k_hist = _normal_bf16((spec.seed, 4), (Hs, Hkv, D), spec.value_scale)
+    v_hist = _normal_bf16((spec.seed, 5), (Hs, Hkv, D), spec.value_scale)
     return Batch(spec, q_start, hist_start, table, max_blocks, num_blocks, q, k_new, v_new, k_hist, v_hist)
 
 
