@@ -129,7 +129,7 @@ tc_status tc_kv_append(const tc_plan *plan, const tc_kv_pool *pool, const void *
  * tc_kv_append of the same batch must precede it on the same stream.  Prefill chunks and
  * decode tokens are processed by one kernel launch; sequences whose KV range was split get
  * their partial results combined by a small second launch.  fp32 accumulation, bf16 output
- * rounded to nearest even.  q, out, workspace: DEVICE.  Results are bitwise reproducible
+ * rounded to nearest even.  scale must be positive and finite.  q, out, workspace: DEVICE.  Results are bitwise reproducible
  * for a fixed plan. */
 tc_status tc_mixed_attention(const tc_plan *plan, const tc_kv_pool *pool, const void *q, void *out, float scale,
                              void *workspace, size_t workspace_bytes, void *stream);

@@ -42,7 +42,7 @@ tc_status tc_mixed_attention(const tc_plan *plan, const tc_kv_pool *pool, const 
     if (!q || !out) return fail(TC_ERR_NULL, "q or out is NULL");
     const size_t need = plan->workspace_bytes();
     if (need > 0 && (!workspace || workspace_bytes < need)) return fail(TC_ERR_WORKSPACE, "workspace missing or too small");
-    if (!(scale == scale)) return fail(TC_ERR_ARG, "scale is NaN");
+    if (!(scale > 0.f) || scale > 3.0e38f) return fail(TC_ERR_ARG, "scale must be positive and finite");
     return device_result(tc::launch_attention(plan, pool, q, out, scale, need ? workspace : nullptr, stream),
                          "tc_mixed_attention launch");
 }

@@ -122,52 +122,73 @@ struct PrefillCfg {
     static constexpr int kLdsBytes = 2 * 2 * kTileBytes;            // two stages of K and V
 };
 
+// Page ids of one tile for the pieces this wave copies.  The page index is wave-uniform, so
+// these are scalar loads; they are issued one tile ahead of the data loads that need them.
 template <int D>
-__device__ __forceinline__ void prefill_fetch(const AttnArgs &A, const int32_t *__restrict__ pages, int n_pages,
-                                              int kv_len, int kvh, int tile, u32x4 (&kr)[PrefillCfg<D>::kPieces],
+__device__ __forceinline__ void prefill_page_ids(const int32_t *__restrict__ pages, int n_pages, int tile, int wave,
+                                                 int (&ids)[PrefillCfg<D>::kPieces]) {
+    using C = PrefillCfg<D>;
+    constexpr int kPiecesPerPage = C::kPageBytes / 16;
+#pragma unroll
+    for (int i = 0; i < C::kPieces; i++) {
+        const int b = (wave * 64 + i * kWgThreads) / kPiecesPerPage;
+        ids[i] = pages[min(tile * C::kTilePages + b, n_pages - 1)];
+    }
+}
+
+// Issue the global loads of one K/V tile (16-byte pieces, one page-sized run per wave).
+template <int D>
+__device__ __forceinline__ void prefill_fetch(const AttnArgs &A, int kvh, const int (&ids)[PrefillCfg<D>::kPieces],
+                                              u32x4 (&kr)[PrefillCfg<D>::kPieces], u32x4 (&vr)[PrefillCfg<D>::kPieces]) {
+    using C = PrefillCfg<D>;
+    constexpr int kPiecesPerPage = C::kPageBytes / 16;
+#pragma unroll
+    for (int i = 0; i < C::kPieces; i++) {
+        const int off = (threadIdx.x + i * kWgThreads) % kPiecesPerPage;
+        const int64_t base = ((int64_t)ids[i] * A.Hkv + kvh) * (int64_t)(kBlock * D) + (int64_t)off * 8;
+        kr[i] = *reinterpret_cast<const u32x4 *>(A.k_pool + base);
+        vr[i] = *reinterpret_cast<const u32x4 *>(A.v_pool + base);
+    }
+}
+
+// Write a fetched tile into an LDS stage.  Slots at or past `kv_len` hold undefined bits (the
+// tail of the last page, or a clamped re-read of it for pages past the end); they get
+// probability 0 but must be finite for the MFMA, so V is zeroed there.
+template <int D>
+__device__ __forceinline__ void prefill_stash(char *lds_k, char *lds_v, int tile, int wave, int kv_len,
+                                              const u32x4 (&kr)[PrefillCfg<D>::kPieces],
                                               u32x4 (&vr)[PrefillCfg<D>::kPieces]) {
     using C = PrefillCfg<D>;
     constexpr int kPiecesPerPage = C::kPageBytes / 16;
 #pragma unroll
     for (int i = 0; i < C::kPieces; i++) {
         const int x = threadIdx.x + i * kWgThreads;
-        const int b = x / kPiecesPerPage;
-        const int off = x % kPiecesPerPage;
-        const int page = tile * C::kTilePages + b;
-        u32x4 kk = {0u, 0u, 0u, 0u}, vv = {0u, 0u, 0u, 0u};
-        if (page < n_pages) {
-            const int64_t base = ((int64_t)pages[page] * A.Hkv + kvh) * (int64_t)(kBlock * D);
-            kk = *reinterpret_cast<const u32x4 *>(A.k_pool + base + (int64_t)off * 8);
-            vv = *reinterpret_cast<const u32x4 *>(A.v_pool + base + (int64_t)off * 8);
-            // Slots past the sequence's last token hold undefined bits; they get probability 0
-            // but must still be finite for the MFMA, so zero them in V.
-            const int n_valid = kv_len - page * kBlock;
-            if (n_valid < kBlock) {
-                const int tok0 = (off & 1) * 8;
+        const int b = (wave * 64 + i * kWgThreads) / kPiecesPerPage;
+        const int n_valid = kv_len - (tile * C::kTilePages + b) * kBlock;
+        u32x4 vv = vr[i];
+        if (n_valid < kBlock) {
+            const int tok0 = (x & 1) * 8;
 #pragma unroll
-                for (int e = 0; e < 4; e++) {
-                    uint32_t w = vv[e];
-                    if (tok0 + 2 * e >= n_valid) w &= 0xFFFF0000u;
-                    if (tok0 + 2 * e + 1 >= n_valid) w &= 0x0000FFFFu;
-                    vv[e] = w;
-                }
+            for (int e = 0; e < 4; e++) {
+                uint32_t w = vv[e];
+                if (tok0 + 2 * e >= n_valid) w &= 0xFFFF0000u;
+                if (tok0 + 2 * e + 1 >= n_valid) w &= 0x0000FFFFu;
+                vv[e] = w;
             }
         }
-        kr[i] = kk;
-        vr[i] = vv;
+        *reinterpret_cast<u32x4 *>(lds_k + x * 16) = kr[i];
+        *reinterpret_cast<u32x4 *>(lds_v + x * 16) = vv;
     }
 }
 
-template <int D>
-__device__ __forceinline__ void prefill_stash(char *lds_k, char *lds_v, const u32x4 (&kr)[PrefillCfg<D>::kPieces],
-                                              const u32x4 (&vr)[PrefillCfg<D>::kPieces]) {
-    using C = PrefillCfg<D>;
-#pragma unroll
-    for (int i = 0; i < C::kPieces; i++) {
-        const int x = threadIdx.x + i * kWgThreads;
-        *reinterpret_cast<u32x4 *>(lds_k + x * 16) = kr[i];
-        *reinterpret_cast<u32x4 *>(lds_v + x * 16) = vr[i];
-    }
+// max / sum across the two half-waves (lanes l and l ^ 32 hold the two halves of a row).
+__device__ __forceinline__ float half_swap_max(float v) {
+    const auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(v), __float_as_uint(v), false, false);
+    return fmaxf(__uint_as_float(r[0]), __uint_as_float(r[1]));
+}
+__device__ __forceinline__ float half_swap_sum(float v) {
+    const auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(v), __float_as_uint(v), false, false);
+    return __uint_as_float(r[0]) + __uint_as_float(r[1]);
 }
 
 template <int D>
@@ -175,7 +196,8 @@ __device__ void prefill_item(const AttnArgs &A, const int32_t *__restrict__ it, 
     using C = PrefillCfg<D>;
     constexpr int KS = D / 16;  // k-steps of the QK^T product
     constexpr int MT = D / 32;  // 32-row tiles of O^T
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int n = lane & 31, hh = lane >> 5;
     const int kvh = it[PF_KVH], pos0 = it[PF_POS0], npos = it[PF_NPOS], qrow0 = it[PF_QROW0], ctx = it[PF_CTX];
     const int n_pages = it[PF_NPAGES];
@@ -193,6 +215,7 @@ __device__ void prefill_item(const AttnArgs &A, const int32_t *__restrict__ it, 
     const int wave_pmin = ctx + pos0 + r_lo / G, wave_pmax = ctx + pos0 + r_hi / G;
     const int kv_len = ctx + pos0 + npos;  // tokens this workgroup may read (all appended already)
     const int n_tiles = (kv_len - 1) / C::kTileTokens + 1;
+    const float c_log2 = A.scale_log2;
 
     bf16x8 qreg[KS];
 #pragma unroll
@@ -203,11 +226,14 @@ __device__ void prefill_item(const AttnArgs &A, const int32_t *__restrict__ it, 
     for (int c = 0; c < MT; c++)
 #pragma unroll
         for (int r = 0; r < 16; r++) o[c][r] = 0.f;
-    float m_run = -1e30f, l_run = 0.f;
+    float m_run = -1e30f, l_run = 0.f;  // running max (log2 domain) and running sum of this lane's half row
 
     u32x4 kr[C::kPieces], vr[C::kPieces];
-    prefill_fetch<D>(A, pages, n_pages, kv_len, kvh, 0, kr, vr);
-    prefill_stash<D>(lds, lds + 2 * C::kTileBytes, kr, vr);
+    int ids[C::kPieces];
+    prefill_page_ids<D>(pages, n_pages, 0, wave, ids);
+    prefill_fetch<D>(A, kvh, ids, kr, vr);
+    prefill_page_ids<D>(pages, n_pages, 1, wave, ids);
+    prefill_stash<D>(lds, lds + 2 * C::kTileBytes, 0, wave, kv_len, kr, vr);
     __syncthreads();
 
     for (int tile = 0; tile < n_tiles; tile++) {
@@ -215,7 +241,10 @@ __device__ void prefill_item(const AttnArgs &A, const int32_t *__restrict__ it, 
         const char *ks = lds + cur * C::kTileBytes;
         const char *vs = lds + 2 * C::kTileBytes + cur * C::kTileBytes;
         const bool more = tile + 1 < n_tiles;
-        if (more) prefill_fetch<D>(A, pages, n_pages, kv_len, kvh, tile + 1, kr, vr);
+        if (more) {
+            prefill_fetch<D>(A, kvh, ids, kr, vr);
+            prefill_page_ids<D>(pages, n_pages, tile + 2, wave, ids);
+        }
 
         const int tok0 = tile * C::kTileTokens;
         if (tok0 <= wave_pmax) {  // otherwise every (row, token) pair of this wave is masked
@@ -231,38 +260,41 @@ __device__ void prefill_item(const AttnArgs &A, const int32_t *__restrict__ it, 
                     s[mt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qreg[kk], s[mt], 0, 0, 0);
                 }
             }
-            const bool need_mask = tok0 + C::kTileTokens - 1 > wave_pmin;
-            float mx = -1e30f;
+            if (tok0 + C::kTileTokens - 1 > wave_pmin) {  // the diagonal crosses this tile: causal mask
+#pragma unroll
+                for (int mt = 0; mt < 2; mt++)
+#pragma unroll
+                    for (int r = 0; r < 16; r++) {
+                        const int j = tok0 + 32 * mt + 8 * (r >> 2) + 4 * hh + (r & 3);
+                        s[mt][r] = (j <= p_abs) ? s[mt][r] : -INFINITY;
+                    }
+            }
+            float mx = s[0][0];
 #pragma unroll
             for (int mt = 0; mt < 2; mt++)
 #pragma unroll
-                for (int r = 0; r < 16; r++) {
-                    float v = s[mt][r] * A.scale_log2;
-                    if (need_mask) {
-                        const int j = tok0 + 32 * mt + 8 * (r >> 2) + 4 * hh + (r & 3);
-                        v = (j <= p_abs) ? v : -INFINITY;
-                    }
-                    s[mt][r] = v;
-                    mx = fmaxf(mx, v);
-                }
-            mx = fmaxf(mx, xor_lanes(mx, 32));
-            const float m_new = fmaxf(m_run, mx);
-            const float alpha = fast_exp2(m_run - m_new);
-            m_run = m_new;
+                for (int r = 0; r < 16; r++) mx = fmaxf(mx, s[mt][r]);
+            mx = half_swap_max(mx);
+            const float m_new = fmaxf(m_run, mx * c_log2);
+            if (__builtin_amdgcn_ballot_w64(m_new > m_run) != 0) {  // some row's maximum moved: rescale
+                const float alpha = fast_exp2(m_run - m_new);
+                m_run = m_new;
+                l_run *= alpha;
+#pragma unroll
+                for (int c = 0; c < MT; c++)
+#pragma unroll
+                    for (int r = 0; r < 16; r++) o[c][r] *= alpha;
+            }
             float psum = 0.f;
 #pragma unroll
             for (int mt = 0; mt < 2; mt++)
 #pragma unroll
                 for (int r = 0; r < 16; r++) {
-                    const float pv = fast_exp2(s[mt][r] - m_new);
+                    const float pv = fast_exp2(__builtin_fmaf(s[mt][r], c_log2, -m_run));
                     s[mt][r] = pv;
                     psum += pv;
                 }
-            l_run = l_run * alpha + psum;
-#pragma unroll
-            for (int c = 0; c < MT; c++)
-#pragma unroll
-                for (int r = 0; r < 16; r++) o[c][r] *= alpha;
+            l_run += psum;
 #pragma unroll
             for (int b = 0; b < C::kTilePages; b++) {
                 bf16x8 pb;
@@ -278,11 +310,13 @@ __device__ void prefill_item(const AttnArgs &A, const int32_t *__restrict__ it, 
                 }
             }
         }
-        if (more) prefill_stash<D>(lds + (cur ^ 1) * C::kTileBytes, lds + 2 * C::kTileBytes + (cur ^ 1) * C::kTileBytes, kr, vr);
+        if (more)
+            prefill_stash<D>(lds + (cur ^ 1) * C::kTileBytes, lds + 2 * C::kTileBytes + (cur ^ 1) * C::kTileBytes, tile + 1,
+                             wave, kv_len, kr, vr);
         __syncthreads();
     }
 
-    l_run += xor_lanes(l_run, 32);
+    l_run = half_swap_sum(l_run);
     const float inv = 1.f / l_run;
     if (row_valid) {
 #pragma unroll
@@ -306,6 +340,87 @@ __device__ void prefill_item(const AttnArgs &A, const int32_t *__restrict__ it, 
 //   O^T[d][head]    += sum_token V^T[d][token] P^T[token][head]   contraction over the 32 tokens
 //                      of a page pair: lane feeds tokens 4g..4g+3 of either page
 template <int D>
+struct DecodeStage {  // K and V of one page pair, in MFMA A-operand registers
+    u32x4 k[2][D / 32];
+    u32x2 v[2][D / 16];
+};
+
+// KV pages are read exactly once per launch, by one wavefront: stream them past the caches.
+template <int D>
+__device__ __forceinline__ void decode_fetch(const AttnArgs &A, int kvh, int id0, int id1, int j, int g,
+                                             DecodeStage<D> &st) {
+    const int64_t tile_elems = (int64_t)kBlock * D;
+    const int ids[2] = {id0, id1};
+#pragma unroll
+    for (int b = 0; b < 2; b++) {
+        const uint16_t *kb = A.k_pool + ((int64_t)ids[b] * A.Hkv + kvh) * tile_elems;
+        const uint16_t *vb = A.v_pool + ((int64_t)ids[b] * A.Hkv + kvh) * tile_elems;
+#pragma unroll
+        for (int kk = 0; kk < D / 32; kk++)
+            st.k[b][kk] = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(kb + ((4 * kk + g) * kBlock + j) * 8));
+#pragma unroll
+        for (int c = 0; c < D / 16; c++)
+            st.v[b][c] = __builtin_nontemporal_load(reinterpret_cast<const u32x2 *>(vb + (16 * c + j) * kBlock + 4 * g));
+    }
+}
+
+template <int D>
+__device__ __forceinline__ void decode_consume(const AttnArgs &A, DecodeStage<D> &st, const bf16x8 (&qreg)[D / 32],
+                                               int n_valid0, int n_valid1, int g, f32x4 (&o)[D / 16], float &m_run,
+                                               float &l_run) {
+    constexpr int KS = D / 32, MT = D / 16;
+    const int n_valid[2] = {n_valid0, n_valid1};
+    f32x4 s[2];
+#pragma unroll
+    for (int b = 0; b < 2; b++) {
+        s[b] = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int kk = 0; kk < KS; kk++)
+            s[b] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, st.k[b][kk]), qreg[kk], s[b], 0, 0, 0);
+    }
+    if (n_valid1 < kBlock) {  // the split ends inside this pair: mask scores, make V finite
+#pragma unroll
+        for (int b = 0; b < 2; b++) {
+#pragma unroll
+            for (int r = 0; r < 4; r++) s[b][r] = (4 * g + r < n_valid[b]) ? s[b][r] : -INFINITY;
+#pragma unroll
+            for (int c = 0; c < MT; c++) {
+                u32x2 w = st.v[b][c];
+                if (4 * g + 0 >= n_valid[b]) w[0] &= 0xFFFF0000u;
+                if (4 * g + 1 >= n_valid[b]) w[0] &= 0x0000FFFFu;
+                if (4 * g + 2 >= n_valid[b]) w[1] &= 0xFFFF0000u;
+                if (4 * g + 3 >= n_valid[b]) w[1] &= 0x0000FFFFu;
+                st.v[b][c] = w;
+            }
+        }
+    }
+    float mx = fmaxf(fmaxf(fmaxf(s[0][0], s[0][1]), fmaxf(s[0][2], s[0][3])),
+                     fmaxf(fmaxf(s[1][0], s[1][1]), fmaxf(s[1][2], s[1][3])));
+    mx = fmaxf(mx, xor_lanes(mx, 16));
+    mx = half_swap_max(mx);
+    const float m_new = fmaxf(m_run, mx * A.scale_log2);
+    const float alpha = fast_exp2(m_run - m_new);
+    m_run = m_new;
+    bf16x8 pb;
+    float psum = 0.f;
+#pragma unroll
+    for (int b = 0; b < 2; b++)
+#pragma unroll
+        for (int r = 0; r < 4; r++) {
+            const float pv = fast_exp2(__builtin_fmaf(s[b][r], A.scale_log2, -m_new));
+            psum += pv;
+            pb[4 * b + r] = (__bf16)pv;
+        }
+    l_run = l_run * alpha + psum;
+#pragma unroll
+    for (int c = 0; c < MT; c++) {
+        o[c] *= alpha;
+        const u32x4 aw = {st.v[0][c][0], st.v[0][c][1], st.v[1][c][0], st.v[1][c][1]};
+        o[c] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, aw), pb, o[c], 0, 0, 0);
+    }
+}
+
+template <int D>
 __device__ void decode_item(const AttnArgs &A, const int32_t *__restrict__ it) {
     constexpr int KS = D / 32;  // k-steps of K Q^T
     constexpr int MT = D / 16;  // 16-row tiles of O^T
@@ -314,9 +429,10 @@ __device__ void decode_item(const AttnArgs &A, const int32_t *__restrict__ it) {
     const int kvh = it[DC_KVH], t0 = it[DC_BEGIN], t1 = it[DC_END], qrow = it[DC_QROW], slot = it[DC_SLOT];
     const int G = A.G;
     const int page0 = t0 / kBlock;
-    const int n_pg = (t1 - t0 + kBlock - 1) / kBlock;  // 1..64
+    const int n_tok = t1 - t0;
+    const int n_pg = (n_tok + kBlock - 1) / kBlock;  // 1..64
     const int32_t *pages = A.pages + it[DC_PAGEOFF] + page0;
-    const int my_page = pages[min(lane, n_pg - 1)];
+    const int my_page = pages[min(lane, n_pg - 1)];  // lane i holds the id of page i of the split
 
     bf16x8 qreg[KS];
     const int64_t q_off = ((int64_t)qrow * A.Hq + kvh * G + min(j, G - 1)) * D;
@@ -331,80 +447,26 @@ __device__ void decode_item(const AttnArgs &A, const int32_t *__restrict__ it) {
 #pragma unroll
     for (int c = 0; c < MT; c++) o[c] = f32x4{0.f, 0.f, 0.f, 0.f};
     float m_run = -1e30f, l_run = 0.f;
-    const int64_t tile_elems = (int64_t)kBlock * D;
 
-    for (int pp = 0; pp < n_pg; pp += 2) {
-        const bool has1 = pp + 1 < n_pg;
-        const int id0 = __builtin_amdgcn_readlane(my_page, pp);
-        const int id1 = __builtin_amdgcn_readlane(my_page, has1 ? pp + 1 : pp);
-        const uint16_t *kb[2] = {A.k_pool + ((int64_t)id0 * A.Hkv + kvh) * tile_elems,
-                                 A.k_pool + ((int64_t)id1 * A.Hkv + kvh) * tile_elems};
-        const uint16_t *vb[2] = {A.v_pool + ((int64_t)id0 * A.Hkv + kvh) * tile_elems,
-                                 A.v_pool + ((int64_t)id1 * A.Hkv + kvh) * tile_elems};
-        bf16x8 kreg[2][KS];
-        u32x2 vreg[2][MT];
-#pragma unroll
-        for (int b = 0; b < 2; b++) {
-#pragma unroll
-            for (int kk = 0; kk < KS; kk++)
-                kreg[b][kk] = *reinterpret_cast<const bf16x8 *>(kb[b] + ((4 * kk + g) * kBlock + j) * 8);
-#pragma unroll
-            for (int c = 0; c < MT; c++)
-                vreg[b][c] = *reinterpret_cast<const u32x2 *>(vb[b] + (16 * c + j) * kBlock + 4 * g);
-        }
-        f32x4 s[2];
-        float mx = -1e30f;
-#pragma unroll
-        for (int b = 0; b < 2; b++) {
-            s[b] = f32x4{0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-            for (int kk = 0; kk < KS; kk++) s[b] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kreg[b][kk], qreg[kk], s[b], 0, 0, 0);
-            // tokens of this page still inside the split (<= 0 for the phantom second page)
-            const int n_valid = (b == 1 && !has1) ? 0 : t1 - (t0 + (pp + b) * kBlock);
-#pragma unroll
-            for (int r = 0; r < 4; r++) {
-                float v = s[b][r] * A.scale_log2;
-                v = (4 * g + r < n_valid) ? v : -INFINITY;
-                s[b][r] = v;
-                mx = fmaxf(mx, v);
-            }
-            if (n_valid < kBlock) {  // undefined slots must not reach the MFMA as NaN
-#pragma unroll
-                for (int c = 0; c < MT; c++) {
-                    u32x2 w = vreg[b][c];
-                    if (4 * g + 0 >= n_valid) w[0] &= 0xFFFF0000u;
-                    if (4 * g + 1 >= n_valid) w[0] &= 0x0000FFFFu;
-                    if (4 * g + 2 >= n_valid) w[1] &= 0xFFFF0000u;
-                    if (4 * g + 3 >= n_valid) w[1] &= 0x0000FFFFu;
-                    vreg[b][c] = w;
-                }
-            }
-        }
-        mx = fmaxf(mx, xor_lanes(mx, 16));
-        mx = fmaxf(mx, xor_lanes(mx, 32));
-        const float m_new = fmaxf(m_run, mx);
-        const float alpha = fast_exp2(m_run - m_new);
-        m_run = m_new;
-        bf16x8 pb;
-        float psum = 0.f;
-#pragma unroll
-        for (int b = 0; b < 2; b++)
-#pragma unroll
-            for (int r = 0; r < 4; r++) {
-                const float pv = fast_exp2(s[b][r] - m_new);
-                psum += pv;
-                pb[4 * b + r] = (__bf16)pv;
-            }
-        l_run = l_run * alpha + psum;
-#pragma unroll
-        for (int c = 0; c < MT; c++) {
-            o[c] *= alpha;
-            const u32x4 aw = {vreg[0][c][0], vreg[0][c][1], vreg[1][c][0], vreg[1][c][1]};
-            o[c] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, aw), pb, o[c], 0, 0, 0);
+    // Page pairs, two register stages: the loads of pair i+1 are in flight while pair i is
+    // consumed.  A phantom second page (odd page count) re-reads the last page and is masked.
+    DecodeStage<D> sa, sb;
+    const int last = n_pg - 1;
+    decode_fetch<D>(A, kvh, __builtin_amdgcn_readlane(my_page, 0), __builtin_amdgcn_readlane(my_page, min(1, last)), j, g, sa);
+    for (int pp = 0; pp < n_pg; pp += 4) {
+        if (pp + 2 < n_pg)
+            decode_fetch<D>(A, kvh, __builtin_amdgcn_readlane(my_page, pp + 2),
+                            __builtin_amdgcn_readlane(my_page, min(pp + 3, last)), j, g, sb);
+        decode_consume<D>(A, sa, qreg, n_tok - pp * kBlock, n_tok - (pp + 1) * kBlock, g, o, m_run, l_run);
+        if (pp + 2 < n_pg) {
+            if (pp + 4 < n_pg)
+                decode_fetch<D>(A, kvh, __builtin_amdgcn_readlane(my_page, pp + 4),
+                                __builtin_amdgcn_readlane(my_page, min(pp + 5, last)), j, g, sa);
+            decode_consume<D>(A, sb, qreg, n_tok - (pp + 2) * kBlock, n_tok - (pp + 3) * kBlock, g, o, m_run, l_run);
         }
     }
     l_run += xor_lanes(l_run, 16);
-    l_run += xor_lanes(l_run, 32);
+    l_run = half_swap_sum(l_run);
     if (j >= G) return;
     if (slot < 0) {
         const float inv = 1.f / l_run;
