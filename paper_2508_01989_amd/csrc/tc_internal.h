@@ -11,9 +11,10 @@
 namespace tc {
 
 constexpr int kBlock = 16;          // tokens per KV page
-constexpr int kWgThreads = 512;     // threads per workgroup of the fused attention kernel
+constexpr int kWgThreads = 256;     // threads per workgroup of the fused attention kernel
 constexpr int kWgWaves = kWgThreads / 64;
-constexpr int kPrefillRows = 256;   // (position, head) rows per prefill workgroup: 32 per wave
+constexpr int kWgPerCu = 2;         // workgroups of the fused kernel resident per compute unit
+constexpr int kPrefillRows = 32 * kWgWaves;  // (position, head) rows per prefill workgroup: 32 per wave
 constexpr int kItemInts = 8;        // int32 fields per work item
 constexpr int kMaxSplitPages = 64;  // a decode split's page ids fit one wavefront register
 

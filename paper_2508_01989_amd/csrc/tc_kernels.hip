@@ -177,7 +177,15 @@ __device__ __forceinline__ void prefill_stash(char *lds_k, char *lds_v, int tile
             }
         }
         *reinterpret_cast<u32x4 *>(lds_k + x * 16) = kr[i];
-        *reinterpret_cast<u32x4 *>(lds_v + x * 16) = vv;
+        // V^T rows (32 bytes = 16 tokens of one head-dim element) are stored as two 16-byte halves,
+        // half 0 = tokens {0-3, 8-11}, half 1 = tokens {4-7, 12-15}: exactly the 8 contraction slots
+        // the two half-waves feed to the PV MFMA, so each lane needs one 16-byte read.  The halves of
+        // rows 8-15 (mod 16) are swapped so that 16 consecutive rows cover all 64 LDS banks.
+        const int off = x % kPiecesPerPage;
+        const int d = off >> 1, h = off & 1, sw = (d >> 3) & 1;
+        char *row = lds_v + (x / kPiecesPerPage) * C::kPageBytes + d * 32 + h * 8;
+        *reinterpret_cast<u32x2 *>(row + sw * 16) = u32x2{vv[0], vv[1]};
+        *reinterpret_cast<u32x2 *>(row + (sw ^ 1) * 16) = u32x2{vv[2], vv[3]};
     }
 }
 
@@ -216,6 +224,7 @@ __device__ void prefill_item(const AttnArgs &A, const int32_t *__restrict__ it, 
     const int kv_len = ctx + pos0 + npos;  // tokens this workgroup may read (all appended already)
     const int n_tiles = (kv_len - 1) / C::kTileTokens + 1;
     const float c_log2 = A.scale_log2;
+    const int v_lane_off = n * 32 + ((hh ^ ((n >> 3) & 1)) * 16);  // this lane's 16 bytes inside a 32-row V^T tile
 
     bf16x8 qreg[KS];
 #pragma unroll
@@ -302,10 +311,7 @@ __device__ void prefill_item(const AttnArgs &A, const int32_t *__restrict__ it, 
                 for (int e = 0; e < 8; e++) pb[e] = (__bf16)s[b >> 1][8 * (b & 1) + e];
 #pragma unroll
                 for (int c = 0; c < MT; c++) {
-                    const char *vp = vs + b * C::kPageBytes + (32 * c + n) * (kBlock * 2) + hh * 8;
-                    const bf16x4 lo = *reinterpret_cast<const bf16x4 *>(vp);
-                    const bf16x4 hi = *reinterpret_cast<const bf16x4 *>(vp + 16);
-                    const bf16x8 a = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+                    const bf16x8 a = *reinterpret_cast<const bf16x8 *>(vs + b * C::kPageBytes + c * (32 * 32) + v_lane_off);
                     o[c] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, pb, o[c], 0, 0, 0);
                 }
             }
@@ -491,7 +497,7 @@ __device__ void decode_item(const AttnArgs &A, const int32_t *__restrict__ it) {
 }
 
 template <int D>
-__global__ void __launch_bounds__(kWgThreads) mixed_attention_kernel(const AttnArgs A) {
+__global__ void __launch_bounds__(kWgThreads, kWgPerCu) mixed_attention_kernel(const AttnArgs A) {
     extern __shared__ __align__(16) char lds[];
     if ((int)blockIdx.x < A.n_prefill) {
         prefill_item<D>(A, A.prefill + (int64_t)blockIdx.x * kItemInts, lds);

@@ -117,7 +117,7 @@ def test_work_list_covers_the_batch_exactly(tc, idx):
     p = tc.Plan(pool, qs, sp.ctx_len, table, host_only=True)
     info, G, Hkv = p.info, sp.num_q_heads // sp.num_kv_heads, sp.num_kv_heads
     pf, dc, mg = p.items(0), p.items(1), p.items(2)
-    # prefill: every (sequence, KV head) has its positions covered once, in tiles of <= 256/G positions
+    # prefill: every (sequence, KV head) has its positions covered once, in tiles of <= rows_per_prefill_item/G positions
     for s in np.flatnonzero(sp.q_len > 1):
         for h in range(Hkv):
             it = pf[(pf[:, 0] == s) & (pf[:, 1] == h)]
@@ -126,7 +126,7 @@ def test_work_list_covers_the_batch_exactly(tc, idx):
             assert it[-1, 2] + it[-1, 3] == sp.q_len[s] and np.all(it[:, 3] * G <= info.rows_per_prefill_item)
             assert np.all(it[:, 4] == qs[s]) and np.all(it[:, 5] == sp.ctx_len[s])
             assert np.all(it[:, 7] == (sp.kv_len[s] + 15) // 16)
-    assert len(pf) == sum(-(-int(q) // (256 // G)) for q in sp.q_len[sp.q_len > 1]) * Hkv
+    assert len(pf) == sum(-(-int(q) // (info.rows_per_prefill_item // G)) for q in sp.q_len[sp.q_len > 1]) * Hkv
     # heaviest prefill tiles first; KV head is the fastest index
     cost = pf[:, 5] + pf[:, 2] + pf[:, 3]
     assert np.all(np.diff(cost[::Hkv]) <= 0) and np.all(pf[:, 1] == np.arange(len(pf)) % Hkv)
@@ -146,4 +146,4 @@ def test_work_list_covers_the_batch_exactly(tc, idx):
         mine = dc[(dc[:, 0] == m[0]) & (dc[:, 1] == m[1])]
         assert sorted(mine[:, 5].tolist()) == list(range(m[3], m[3] + m[4]))
     assert p.workspace_bytes == info.num_partials * G * (sp.head_dim + 2) * 4
-    assert info.grid_blocks == info.num_prefill_items + -(-info.num_decode_items // 8)
+    assert info.grid_blocks == info.num_prefill_items + -(-info.num_decode_items // (info.block_threads // 64))
