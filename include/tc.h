@@ -21,8 +21,9 @@
  *   q, out        [T][Hq][D]      packed query rows of the batch, T = q_start[num_seqs]
  *   k_new, v_new  [T][Hkv][D]     keys / values of the same rows
  *   k_pool        [num_blocks][Hkv][D/8][B][8]
- *   v_pool        [num_blocks][Hkv][D][B]
- * Token j of sequence s lives in pool block block_table[s][j / B], slot j % B.
+ *   v_pool        [num_blocks][Hkv][D][B], token index t of a block at position slot(t) = t with
+ *                 bits 2 and 3 exchanged (a 16-token row reads 0-3, 8-11, 4-7, 12-15)
+ * Token j of sequence s lives in pool block block_table[s][j / B], token index j % B.
  * Query head h reads KV head h / G.
  */
 #ifndef TC_H

@@ -22,8 +22,9 @@
  *   K pool  [num_blocks][Hkv][D/8][B][8]   element (blk,h,tok,d) ->
  *           (((blk*Hkv + h)*(D/8) + d/8)*B + tok)*8 + d%8
  *   V pool  [num_blocks][Hkv][D][B]        element (blk,h,tok,d) ->
- *           ((blk*Hkv + h)*D + d)*B + tok
- * Token j of sequence s lives in block table[s][j / B] at slot j % B.
+ *           ((blk*Hkv + h)*D + d)*B + slot(tok),  slot(tok) = tok with bits 2 and 3
+ *           exchanged (a row holds tokens 0-3, 8-11, 4-7, 12-15 in that order)
+ * Token j of sequence s lives in block table[s][j / B] at token index j % B.
  *
  * Parity pins: every function here is pinned by tests/test_oracle_pins.py
  * (brute force, closed forms, a library routine, invariants).
@@ -56,7 +57,8 @@ static int64_t k_index(const shape_t *sh, int64_t blk, int h, int tok, int d)
 
 static int64_t v_index(const shape_t *sh, int64_t blk, int h, int tok, int d)
 {
-    return ((blk * sh->Hkv + h) * sh->D + d) * sh->B + tok;
+    int slot = (tok & ~12) | ((tok & 4) << 1) | ((tok & 8) >> 1);
+    return ((blk * sh->Hkv + h) * sh->D + d) * sh->B + slot;
 }
 
 int tco_num_threads(void)

@@ -19,6 +19,10 @@
 
 #include "tc_internal.h"
 
+#ifndef TC_ROWSUM_MFMA
+#define TC_ROWSUM_MFMA 0
+#endif
+
 namespace tc {
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
@@ -41,6 +45,11 @@ struct AttnArgs {
     float scale_log2;        // softmax scale times log2(e)
 };
 
+// Position of token `tok` (0..15) inside a 16-token row of the V pool: bits 2 and 3 exchanged, i.e.
+// the row holds tokens {0-3, 8-11, 4-7, 12-15}.  Each 16-byte half of a row is then exactly the
+// eight contraction slots one half-wave feeds to the 32x32x16 MFMA.  The map is its own inverse.
+__host__ __device__ __forceinline__ int v_slot(int tok) { return (tok & 3) | ((tok & 4) << 1) | ((tok & 8) >> 1); }
+
 __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
 
 __device__ __forceinline__ float xor_lanes(float v, int mask) { return __shfl_xor(v, mask, 64); }
@@ -50,7 +59,7 @@ __device__ __forceinline__ float xor_lanes(float v, int mask) { return __shfl_xo
 // ------------------------------------------------------------------------------------
 // One thread moves 8 consecutive head-dim elements (16 bytes) of K and of V of one
 // (token, KV head).  K keeps the 8 elements together; V is stored token-minor, so its 8
-// elements go to 8 rows of the [D][16] tile.
+// elements go to 8 rows of the [D][16] tile, at the token's slot v_slot(tok) of each row.
 template <int D>
 __global__ void __launch_bounds__(256) kv_append_kernel(uint16_t *__restrict__ k_pool, uint16_t *__restrict__ v_pool,
                                                         const uint16_t *__restrict__ k_new,
@@ -71,7 +80,7 @@ __global__ void __launch_bounds__(256) kv_append_kernel(uint16_t *__restrict__ k
     const u32x4 vv = *reinterpret_cast<const u32x4 *>(v_new + src);
     const int64_t tile = (blk * Hkv + h) * (int64_t)(kBlock * D);
     *reinterpret_cast<u32x4 *>(k_pool + tile + ((int64_t)c * kBlock + tok) * 8) = kv;
-    uint16_t *vdst = v_pool + tile + (int64_t)(c * 8) * kBlock + tok;
+    uint16_t *vdst = v_pool + tile + (int64_t)(c * 8) * kBlock + v_slot(tok);
 #pragma unroll
     for (int e = 0; e < 8; e++) {
         const uint32_t w = vv[e >> 1];
@@ -96,7 +105,7 @@ __global__ void __launch_bounds__(256) kv_gather_kernel(const uint16_t *__restri
     const int64_t tile = (blk * Hkv + h) * (int64_t)(kBlock * D);
     const int64_t dst = ((int64_t)j * Hkv + h) * D + c * 8;
     *reinterpret_cast<u32x4 *>(k_out + dst) = *reinterpret_cast<const u32x4 *>(k_pool + tile + ((int64_t)c * kBlock + tok) * 8);
-    const uint16_t *vsrc = v_pool + tile + (int64_t)(c * 8) * kBlock + tok;
+    const uint16_t *vsrc = v_pool + tile + (int64_t)(c * 8) * kBlock + v_slot(tok);
     u32x4 vv;
 #pragma unroll
     for (int e = 0; e < 4; e++) vv[e] = (uint32_t)vsrc[(2 * e) * kBlock] | ((uint32_t)vsrc[(2 * e + 1) * kBlock] << 16);
@@ -112,6 +121,8 @@ __global__ void __launch_bounds__(256) kv_gather_kernel(const uint16_t *__restri
 //   S^T[token][row]  = sum_d K[token][d] Q[row][d]        (A = K from LDS, B = Q in registers)
 //   O^T[d][row]     += sum_token V^T[d][token] P^T[token][row]   (A = V^T from LDS, B = P)
 // with the online softmax (running max m, running sum l) kept per row in fp32.
+constexpr bool kRowSumOnMfma = TC_ROWSUM_MFMA;
+
 template <int D>
 struct PrefillCfg {
     static constexpr int kTileTokens = 64;
@@ -136,58 +147,59 @@ __device__ __forceinline__ void prefill_page_ids(const int32_t *__restrict__ pag
     }
 }
 
-// Issue the global loads of one K/V tile (16-byte pieces, one page-sized run per wave).
+// Copy one K/V tile (four pages of one KV head) from the pool straight into an LDS stage with
+// direct-to-LDS loads: lane L of a wave deposits its 16 bytes at (wave-uniform base) + 16 L, so
+// each wave copies 1 KiB runs.  K pages are copied verbatim.  A V^T page is copied row by row
+// (32 bytes = 16 token slots of one head-dim element) with the two 16-byte halves of rows 8-15
+// (mod 16) exchanged, so that the operand reads of 16 consecutive rows cover all 64 LDS banks.
 template <int D>
 __device__ __forceinline__ void prefill_fetch(const AttnArgs &A, int kvh, const int (&ids)[PrefillCfg<D>::kPieces],
-                                              u32x4 (&kr)[PrefillCfg<D>::kPieces], u32x4 (&vr)[PrefillCfg<D>::kPieces]) {
+                                              char *lds_k, char *lds_v, int wave, int lane) {
     using C = PrefillCfg<D>;
     constexpr int kPiecesPerPage = C::kPageBytes / 16;
+    typedef const __attribute__((address_space(1))) void *gptr_t;
+    typedef __attribute__((address_space(3))) void *lptr_t;
 #pragma unroll
     for (int i = 0; i < C::kPieces; i++) {
-        const int off = (threadIdx.x + i * kWgThreads) % kPiecesPerPage;
-        const int64_t base = ((int64_t)ids[i] * A.Hkv + kvh) * (int64_t)(kBlock * D) + (int64_t)off * 8;
-        kr[i] = *reinterpret_cast<const u32x4 *>(A.k_pool + base);
-        vr[i] = *reinterpret_cast<const u32x4 *>(A.v_pool + base);
+        const int x0 = wave * 64 + i * kWgThreads;  // first 16-byte piece of this wave's run
+        const int off = x0 % kPiecesPerPage + lane;
+        const int64_t base = ((int64_t)__builtin_amdgcn_readfirstlane(ids[i]) * A.Hkv + kvh) * (int64_t)(kBlock * D);
+        const int d = off >> 1, half = (off & 1) ^ ((d >> 3) & 1);
+        __builtin_amdgcn_global_load_lds((gptr_t)(A.k_pool + base + off * 8), (lptr_t)(lds_k + x0 * 16), 16, 0, 0);
+        __builtin_amdgcn_global_load_lds((gptr_t)(A.v_pool + base + d * kBlock + half * 8), (lptr_t)(lds_v + x0 * 16), 16, 0, 0);
     }
 }
 
-// Write a fetched tile into an LDS stage.  Slots at or past `kv_len` hold undefined bits (the
-// tail of the last page, or a clamped re-read of it for pages past the end); they get
-// probability 0 but must be finite for the MFMA, so V is zeroed there.
+// After this thread's own direct-to-LDS loads of `tile` have landed: slots at or past `kv_len`
+// hold undefined bits (the tail of the last page, or a clamped re-read of it for pages past the
+// end).  They get probability 0 but must be finite for the MFMA, so zero them in the V stage.
+// Each thread patches only the 16-byte pieces it loaded itself, so no extra barrier is needed.
 template <int D>
-__device__ __forceinline__ void prefill_stash(char *lds_k, char *lds_v, int tile, int wave, int kv_len,
-                                              const u32x4 (&kr)[PrefillCfg<D>::kPieces],
-                                              u32x4 (&vr)[PrefillCfg<D>::kPieces]) {
+__device__ __forceinline__ void prefill_fix_tail(char *lds_v, int tile, int wave, int lane, int kv_len) {
     using C = PrefillCfg<D>;
     constexpr int kPiecesPerPage = C::kPageBytes / 16;
 #pragma unroll
     for (int i = 0; i < C::kPieces; i++) {
-        const int x = threadIdx.x + i * kWgThreads;
-        const int b = (wave * 64 + i * kWgThreads) / kPiecesPerPage;
-        const int n_valid = kv_len - (tile * C::kTilePages + b) * kBlock;
-        u32x4 vv = vr[i];
+        const int x0 = wave * 64 + i * kWgThreads;
+        const int n_valid = kv_len - (tile * C::kTilePages + x0 / kPiecesPerPage) * kBlock;
         if (n_valid < kBlock) {
-            const int tok0 = (x & 1) * 8;
+            const int off = x0 % kPiecesPerPage + lane;
+            const int d = off >> 1, half = (off & 1) ^ ((d >> 3) & 1);
+            u32x4 *piece = reinterpret_cast<u32x4 *>(lds_v + (x0 + lane) * 16);
+            u32x4 vv = *piece;
 #pragma unroll
             for (int e = 0; e < 4; e++) {
                 uint32_t w = vv[e];
-                if (tok0 + 2 * e >= n_valid) w &= 0xFFFF0000u;
-                if (tok0 + 2 * e + 1 >= n_valid) w &= 0x0000FFFFu;
+                if (v_slot(half * 8 + 2 * e) >= n_valid) w &= 0xFFFF0000u;
+                if (v_slot(half * 8 + 2 * e + 1) >= n_valid) w &= 0x0000FFFFu;
                 vv[e] = w;
             }
+            *piece = vv;
         }
-        *reinterpret_cast<u32x4 *>(lds_k + x * 16) = kr[i];
-        // V^T rows (32 bytes = 16 tokens of one head-dim element) are stored as two 16-byte halves,
-        // half 0 = tokens {0-3, 8-11}, half 1 = tokens {4-7, 12-15}: exactly the 8 contraction slots
-        // the two half-waves feed to the PV MFMA, so each lane needs one 16-byte read.  The halves of
-        // rows 8-15 (mod 16) are swapped so that 16 consecutive rows cover all 64 LDS banks.
-        const int off = x % kPiecesPerPage;
-        const int d = off >> 1, h = off & 1, sw = (d >> 3) & 1;
-        char *row = lds_v + (x / kPiecesPerPage) * C::kPageBytes + d * 32 + h * 8;
-        *reinterpret_cast<u32x2 *>(row + sw * 16) = u32x2{vv[0], vv[1]};
-        *reinterpret_cast<u32x2 *>(row + (sw ^ 1) * 16) = u32x2{vv[2], vv[3]};
     }
 }
+
+__device__ __forceinline__ void wait_all_loads() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); }
 
 // max / sum across the two half-waves (lanes l and l ^ 32 hold the two halves of a row).
 __device__ __forceinline__ float half_swap_max(float v) {
@@ -235,14 +247,23 @@ __device__ void prefill_item(const AttnArgs &A, const int32_t *__restrict__ it, 
     for (int c = 0; c < MT; c++)
 #pragma unroll
         for (int r = 0; r < 16; r++) o[c][r] = 0.f;
-    float m_run = -1e30f, l_run = 0.f;  // running max (log2 domain) and running sum of this lane's half row
+    float m_run = -1e30f;  // running row maximum, log2 domain
+    // Running row sum.  kRowSumOnMfma: accumulate it on the matrix cores as ones^T P^T (every
+    // element of lsum holds the sum over both half-waves); otherwise add on the vector ALU.
+    f32x16 lsum;
+#pragma unroll
+    for (int r = 0; r < 16; r++) lsum[r] = 0.f;
+    float l_run = 0.f;
+    bf16x8 ones;
+#pragma unroll
+    for (int e = 0; e < 8; e++) ones[e] = (__bf16)1.0f;
 
-    u32x4 kr[C::kPieces], vr[C::kPieces];
     int ids[C::kPieces];
     prefill_page_ids<D>(pages, n_pages, 0, wave, ids);
-    prefill_fetch<D>(A, kvh, ids, kr, vr);
+    prefill_fetch<D>(A, kvh, ids, lds, lds + 2 * C::kTileBytes, wave, lane);
     prefill_page_ids<D>(pages, n_pages, 1, wave, ids);
-    prefill_stash<D>(lds, lds + 2 * C::kTileBytes, 0, wave, kv_len, kr, vr);
+    wait_all_loads();
+    if (kv_len < C::kTileTokens) prefill_fix_tail<D>(lds + 2 * C::kTileBytes, 0, wave, lane, kv_len);
     __syncthreads();
 
     for (int tile = 0; tile < n_tiles; tile++) {
@@ -250,8 +271,8 @@ __device__ void prefill_item(const AttnArgs &A, const int32_t *__restrict__ it, 
         const char *ks = lds + cur * C::kTileBytes;
         const char *vs = lds + 2 * C::kTileBytes + cur * C::kTileBytes;
         const bool more = tile + 1 < n_tiles;
-        if (more) {
-            prefill_fetch<D>(A, kvh, ids, kr, vr);
+        if (more) {  // stage cur^1 was last read before the barrier that ended the previous iteration
+            prefill_fetch<D>(A, kvh, ids, lds + (cur ^ 1) * C::kTileBytes, lds + 2 * C::kTileBytes + (cur ^ 1) * C::kTileBytes, wave, lane);
             prefill_page_ids<D>(pages, n_pages, tile + 2, wave, ids);
         }
 
@@ -288,7 +309,12 @@ __device__ void prefill_item(const AttnArgs &A, const int32_t *__restrict__ it, 
             if (__builtin_amdgcn_ballot_w64(m_new > m_run) != 0) {  // some row's maximum moved: rescale
                 const float alpha = fast_exp2(m_run - m_new);
                 m_run = m_new;
-                l_run *= alpha;
+                if (kRowSumOnMfma) {
+#pragma unroll
+                    for (int r = 0; r < 16; r++) lsum[r] *= alpha;
+                } else {
+                    l_run *= alpha;
+                }
 #pragma unroll
                 for (int c = 0; c < MT; c++)
 #pragma unroll
@@ -301,14 +327,15 @@ __device__ void prefill_item(const AttnArgs &A, const int32_t *__restrict__ it, 
                 for (int r = 0; r < 16; r++) {
                     const float pv = fast_exp2(__builtin_fmaf(s[mt][r], c_log2, -m_run));
                     s[mt][r] = pv;
-                    psum += pv;
+                    if (!kRowSumOnMfma) psum += pv;
                 }
-            l_run += psum;
+            if (!kRowSumOnMfma) l_run += psum;
 #pragma unroll
             for (int b = 0; b < C::kTilePages; b++) {
                 bf16x8 pb;
 #pragma unroll
                 for (int e = 0; e < 8; e++) pb[e] = (__bf16)s[b >> 1][8 * (b & 1) + e];
+                if (kRowSumOnMfma) lsum = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ones, pb, lsum, 0, 0, 0);
 #pragma unroll
                 for (int c = 0; c < MT; c++) {
                     const bf16x8 a = *reinterpret_cast<const bf16x8 *>(vs + b * C::kPageBytes + c * (32 * 32) + v_lane_off);
@@ -316,13 +343,13 @@ __device__ void prefill_item(const AttnArgs &A, const int32_t *__restrict__ it, 
                 }
             }
         }
-        if (more)
-            prefill_stash<D>(lds + (cur ^ 1) * C::kTileBytes, lds + 2 * C::kTileBytes + (cur ^ 1) * C::kTileBytes, tile + 1,
-                             wave, kv_len, kr, vr);
+        wait_all_loads();
+        if (more && (tile + 2) * C::kTileTokens > kv_len)
+            prefill_fix_tail<D>(lds + 2 * C::kTileBytes + (cur ^ 1) * C::kTileBytes, tile + 1, wave, lane, kv_len);
         __syncthreads();
     }
 
-    l_run = half_swap_sum(l_run);
+    l_run = kRowSumOnMfma ? lsum[0] : half_swap_sum(l_run);
     const float inv = 1.f / l_run;
     if (row_valid) {
 #pragma unroll
@@ -366,7 +393,7 @@ __device__ __forceinline__ void decode_fetch(const AttnArgs &A, int kvh, int id0
             st.k[b][kk] = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(kb + ((4 * kk + g) * kBlock + j) * 8));
 #pragma unroll
         for (int c = 0; c < D / 16; c++)
-            st.v[b][c] = __builtin_nontemporal_load(reinterpret_cast<const u32x2 *>(vb + (16 * c + j) * kBlock + 4 * g));
+            st.v[b][c] = __builtin_nontemporal_load(reinterpret_cast<const u32x2 *>(vb + (16 * c + j) * kBlock + v_slot(4 * g)));
     }
 }
 
@@ -496,14 +523,33 @@ __device__ void decode_item(const AttnArgs &A, const int32_t *__restrict__ it) {
     }
 }
 
+struct AttnScalars {
+    int n_prefill, n_decode;
+    int Hq, Hkv, G;
+    float scale_log2;
+};
+
+// The pointers are separate __restrict__ kernel arguments (not struct members) so that the
+// compiler knows the work list and the page table are never written and can fetch them with
+// scalar loads.
 template <int D>
-__global__ void __launch_bounds__(kWgThreads, kWgPerCu) mixed_attention_kernel(const AttnArgs A) {
+__global__ void __launch_bounds__(kWgThreads, kWgPerCu)
+    mixed_attention_kernel(const uint16_t *__restrict__ k_pool, const uint16_t *__restrict__ v_pool,
+                           const uint16_t *__restrict__ q, uint16_t *__restrict__ out, const int32_t *__restrict__ pages,
+                           const int32_t *__restrict__ prefill, const int32_t *__restrict__ decode,
+                           float *__restrict__ ws_o, float *__restrict__ ws_ml, const AttnScalars sc) {
     extern __shared__ __align__(16) char lds[];
+    AttnArgs A;
+    A.k_pool = k_pool; A.v_pool = v_pool; A.q = q; A.out = out; A.pages = pages; A.prefill = prefill; A.decode = decode;
+    A.ws_o = ws_o; A.ws_ml = ws_ml;
+    A.n_prefill = sc.n_prefill; A.n_decode = sc.n_decode; A.Hq = sc.Hq; A.Hkv = sc.Hkv; A.G = sc.G;
+    A.scale_log2 = sc.scale_log2;
     if ((int)blockIdx.x < A.n_prefill) {
-        prefill_item<D>(A, A.prefill + (int64_t)blockIdx.x * kItemInts, lds);
+        prefill_item<D>(A, prefill + (int64_t)blockIdx.x * kItemInts, lds);
     } else {
-        const int idx = ((int)blockIdx.x - A.n_prefill) * kWgWaves + (int)(threadIdx.x >> 6);
-        if (idx < A.n_decode) decode_item<D>(A, A.decode + (int64_t)idx * kItemInts);
+        const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+        const int idx = ((int)blockIdx.x - A.n_prefill) * kWgWaves + wave;
+        if (idx < A.n_decode) decode_item<D>(A, decode + (int64_t)idx * kItemInts);
     }
 }
 
@@ -598,7 +644,10 @@ static int launch_attention_d(const tc_plan *p, const AttnArgs &A, hipStream_t s
         lds_ok = true;
     }
     const int grid = p->grid_blocks();
-    if (grid > 0) mixed_attention_kernel<D><<<grid, kWgThreads, p->n_prefill > 0 ? lds : 0, st>>>(A);
+    const AttnScalars sc = {A.n_prefill, A.n_decode, A.Hq, A.Hkv, A.G, A.scale_log2};
+    if (grid > 0)
+        mixed_attention_kernel<D><<<grid, kWgThreads, p->n_prefill > 0 ? lds : 0, st>>>(A.k_pool, A.v_pool, A.q, A.out, A.pages, A.prefill,
+                                                                                 A.decode, A.ws_o, A.ws_ml, sc);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return (int)e;
     if (p->n_merge > 0)
