@@ -22,38 +22,63 @@ sys.path.insert(0, ROOT)
 
 PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA
 PEAK_HBM_GBS = 8000.0       # MI355X HBM3E
+TRAFFIC_FILE = os.path.join(ROOT, "profiles", "hbm_traffic.txt")
+
+
+def measured_traffic(workload):
+    """HBM bytes per launch of the attention kernel from the committed rocprofv3 counter summary
+    (FETCH_SIZE + WRITE_SIZE, scaled by the plain-copy calibration), or None if not recorded."""
+    try:
+        for line in open(TRAFFIC_FILE):
+            f = line.split()
+            if len(f) >= 4 and f[0] == workload and f[1] == "mixed_attention_kernel":
+                return float(f[2]) + float(f[3])
+    except OSError:
+        pass
+    return None
 WORKLOADS = ["tiny", "prefill_heavy", "decode_heavy", "pure_decode", "long_prompt"]
 
 
-def cpu_baseline(batch, work, budget_rows=96):
-    """Time the fp64 oracle, as it stands, on a bounded sample of the same batch: the KV
-    append of the iteration plus attention for a stratified sample of query rows; scale by
-    (query,key) pairs to a whole-batch rate."""
+def cpu_baseline(batch, work, target_s=15.0):
+    """Time the fp64 oracle, as it stands, on the same batch: the KV append of the iteration plus
+    attention for evenly spaced query rows (all heads).  A short probe sizes the sample to about
+    `target_s` seconds of CPU work; if the whole batch fits in twice that, the whole batch is run.
+    A sampled time is scaled by (query,key) pairs to a whole-batch rate."""
     import oracle
     sp = batch.spec
     k_pool, v_pool = oracle.new_pool(batch.num_blocks, sp.num_kv_heads, sp.head_dim, sp.block_size)
-    keep = np.flatnonzero(sp.ctx_len > 0)
-    if len(keep):
+    if int(batch.hist_start[-1]) > 0:
         oracle.kv_append(k_pool, v_pool, sp.num_kv_heads, sp.head_dim, sp.block_size, batch.hist_start.astype(np.int32),
                          np.zeros(sp.num_seqs, np.int32), batch.block_table, batch.k_hist, batch.v_hist)
     T = batch.total_q
-    rows = np.unique(np.linspace(0, T - 1, min(budget_rows, T)).round().astype(np.int32))
+    owner = np.repeat(np.arange(sp.num_seqs), sp.q_len)
+    pos = sp.ctx_len[owner] + (np.arange(T) - batch.q_start[owner])
+
+    def attend(rows):
+        t0 = time.perf_counter()
+        oracle.attention(k_pool, v_pool, sp.num_q_heads, sp.num_kv_heads, sp.head_dim, sp.block_size, batch.q_start,
+                         sp.ctx_len, batch.block_table, batch.q, sp.scale, rows)
+        return time.perf_counter() - t0, int((pos[rows].astype(np.int64) + 1).sum())
+
     t0 = time.perf_counter()
     oracle.kv_append(k_pool, v_pool, sp.num_kv_heads, sp.head_dim, sp.block_size, batch.q_start, sp.ctx_len,
                      batch.block_table, batch.k_new, batch.v_new)
     t_append = time.perf_counter() - t0
-    t0 = time.perf_counter()
-    oracle.attention(k_pool, v_pool, sp.num_q_heads, sp.num_kv_heads, sp.head_dim, sp.block_size, batch.q_start,
-                     sp.ctx_len, batch.block_table, batch.q, sp.scale, rows)
-    t_attn = time.perf_counter() - t0
-    owner = np.repeat(np.arange(sp.num_seqs), sp.q_len)
-    pos = sp.ctx_len[owner] + (np.arange(T) - batch.q_start[owner])
-    pairs_sample = int((pos[rows].astype(np.int64) + 1).sum())
+    probe = np.unique(np.linspace(0, T - 1, min(32, T)).round().astype(np.int32))
+    t_probe, pairs_probe = attend(probe)
+    full_est = t_probe * work["pairs_per_head"] / pairs_probe
+    if full_est <= 2 * target_s:
+        rows = np.arange(T, dtype=np.int32)
+    else:
+        n = int(max(32, min(T, len(probe) * target_s / max(t_probe, 1e-6))))
+        rows = np.unique(np.linspace(0, T - 1, n).round().astype(np.int32))
+    t_attn, pairs_sample = attend(rows)
     est = t_append + t_attn * work["pairs_per_head"] / pairs_sample
+    what = "the whole batch" if len(rows) == T else f"{len(rows)} evenly spaced query rows of {T}"
     return {"value": T / est, "unit": "tokens/s", "cores": oracle.num_threads(), "kind": "oracle",
-            "sample": f"fp64 oracle: KV append of all {T} rows ({t_append:.3f} s) + attention of {len(rows)} evenly spaced "
-                      f"query rows, all heads ({t_attn:.2f} s, {pairs_sample} of {work['pairs_per_head']} (q,k) pairs per head); "
-                      f"time scaled by pairs to the whole batch ({est:.1f} s)"}
+            "sample": f"fp64 oracle: KV append of all {T} rows ({t_append:.3f} s) + attention of {what}, all heads "
+                      f"({t_attn:.2f} s, {pairs_sample} of {work['pairs_per_head']} (q,k) pairs per head); "
+                      f"{'measured' if len(rows) == T else 'time scaled by pairs to the whole batch'} ({est:.1f} s)"}
 
 
 def main():
@@ -63,6 +88,8 @@ def main():
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--workload", default="prefill_heavy", choices=WORKLOADS)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="run a plain 1 GiB device copy three times and exit (counter calibration under rocprofv3 --pmc)")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build runs on one GPU only (independent instances shard by data, "
@@ -75,6 +102,15 @@ def main():
     from paper_2508_01989_amd.harness import DeviceBatch
 
     tc.lib()  # fails loudly if the HIP library is not built
+    if args.calibrate_copy:
+        n = 1 << 28
+        src = torch.arange(n, dtype=torch.int32, device="cuda:0")
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        print(json.dumps({"calibrate_copy_bytes_each_way": n * 4, "copies": 3}))
+        return
     idx = WORKLOADS.index(args.workload)
     spec = W.config_spec(idx)
     batch = W.make_batch(spec)
@@ -119,6 +155,7 @@ def main():
         achieved = attn_bytes / (attn_ms * 1e-3) / 1e9
         roofline = {"bound": "hbm", "achieved": achieved, "peak": PEAK_HBM_GBS, "unit": "GB/s",
                     "frac": achieved / PEAK_HBM_GBS, "traffic": None}
+    roofline["traffic"] = measured_traffic(args.workload)
     roofline.update({"kernel": "mixed_attention_kernel (+ split_merge_kernel)", "kernel_ms": attn_ms,
                      "algorithmic_flops": work["flops"], "algorithmic_bytes": work["bytes"]})
 
