@@ -16,6 +16,7 @@ constexpr int kWgWaves = kWgThreads / 64;
 constexpr int kWgPerCu = 2;         // workgroups of the fused kernel resident per compute unit
 constexpr int kPrefillRows = 32 * kWgWaves;  // (position, head) rows per prefill workgroup: 32 per wave
 constexpr int kItemInts = 8;        // int32 fields per work item
+constexpr int kAppendInts = 4;      // int32 fields per append segment: first packed row, tokens, first token index, pool block
 constexpr int kMaxSplitPages = 64;  // a decode split's page ids fit one wavefront register
 
 // Field indices of work items (see tc_plan_copy_items in tc.h).
@@ -38,7 +39,8 @@ struct tc_plan {
     std::vector<int32_t> q_start, ctx_len, page_off;  // host copies
     // One int32 buffer uploaded as a whole; offsets (in int32 units) of its sections.
     std::vector<int32_t> host;
-    size_t off_slot = 0, off_pages = 0, off_prefill = 0, off_decode = 0, off_merge = 0;
+    size_t off_append = 0, off_pages = 0, off_prefill = 0, off_decode = 0, off_merge = 0;
+    int n_append = 0;  // (sequence, page) segments written by the append
     int32_t *dev = nullptr;  // device copy of `host`, nullptr for host-only plans
     int device = -1;
 

@@ -17,6 +17,8 @@
 // without any transposition.
 #include <hip/hip_runtime.h>
 
+#include <algorithm>
+
 #include "tc_internal.h"
 
 #ifndef TC_ROWSUM_MFMA
@@ -57,34 +59,49 @@ __device__ __forceinline__ float xor_lanes(float v, int mask) { return __shfl_xo
 // ------------------------------------------------------------------------------------
 // KV append / gather
 // ------------------------------------------------------------------------------------
-// One thread moves 8 consecutive head-dim elements (16 bytes) of K and of V of one
-// (token, KV head).  K keeps the 8 elements together; V is stored token-minor, so its 8
-// elements go to 8 rows of the [D][16] tile, at the token's slot v_slot(tok) of each row.
+// One workgroup writes the rows one sequence adds to one page (1..16 consecutive token indices) for
+// one KV head.  K: a thread copies the 16 bytes (8 head-dim elements) of one token.  V is
+// token-minor in the pool, so a thread owns one head-dim element and four consecutive token
+// slots: it reads up to four 2-byte values (adjacent lanes read adjacent elements, so the reads
+// coalesce) and, when all four tokens are new, stores them as one 8-byte word; otherwise it stores
+// only the new tokens, 2 bytes each, so every other pool byte stays untouched.
 template <int D>
-__global__ void __launch_bounds__(256) kv_append_kernel(uint16_t *__restrict__ k_pool, uint16_t *__restrict__ v_pool,
-                                                        const uint16_t *__restrict__ k_new,
-                                                        const uint16_t *__restrict__ v_new,
-                                                        const int32_t *__restrict__ slot_of_row, int T, int Hkv) {
-    constexpr int CH = D / 8;
-    const int64_t gid = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-    const int64_t total = (int64_t)T * Hkv * CH;
-    if (gid >= total) return;
-    const int c = (int)(gid % CH);
-    const int h = (int)((gid / CH) % Hkv);
-    const int t = (int)(gid / ((int64_t)CH * Hkv));
-    const int slot = slot_of_row[t];
-    const int64_t blk = slot / kBlock;
-    const int tok = slot % kBlock;
-    const int64_t src = ((int64_t)t * Hkv + h) * D + c * 8;
-    const u32x4 kv = *reinterpret_cast<const u32x4 *>(k_new + src);
-    const u32x4 vv = *reinterpret_cast<const u32x4 *>(v_new + src);
-    const int64_t tile = (blk * Hkv + h) * (int64_t)(kBlock * D);
-    *reinterpret_cast<u32x4 *>(k_pool + tile + ((int64_t)c * kBlock + tok) * 8) = kv;
-    uint16_t *vdst = v_pool + tile + (int64_t)(c * 8) * kBlock + v_slot(tok);
+__global__ void __launch_bounds__(4 * D) kv_append_kernel(uint16_t *__restrict__ k_pool, uint16_t *__restrict__ v_pool,
+                                                          const uint16_t *__restrict__ k_new,
+                                                          const uint16_t *__restrict__ v_new,
+                                                          const int32_t *__restrict__ segments, int Hkv) {
+    const int32_t *seg = segments + (int64_t)blockIdx.x * kAppendInts;
+    const int h = blockIdx.y;
+    const int row0 = seg[0], n_tok = seg[1], tok0 = seg[2];
+    const int64_t tile = ((int64_t)seg[3] * Hkv + h) * (int64_t)(kBlock * D);
+    const int tid = threadIdx.x;
+    // ---- V: thread = (slot group g, element d); slots 4g..4g+3 hold tokens t(g)..t(g)+3, t = v_slot(4g)
+    {
+        const int d = tid % D, g = tid / D;
+        const int t_first = v_slot(4 * g);  // token index stored in slot 4g
+        uint16_t val[4];
+        bool have[4];
 #pragma unroll
-    for (int e = 0; e < 8; e++) {
-        const uint32_t w = vv[e >> 1];
-        vdst[e * kBlock] = (uint16_t)((e & 1) ? (w >> 16) : (w & 0xFFFFu));
+        for (int e = 0; e < 4; e++) {
+            const int t = t_first + e;
+            have[e] = t >= tok0 && t < tok0 + n_tok;
+            val[e] = have[e] ? v_new[((int64_t)(row0 + t - tok0) * Hkv + h) * D + d] : (uint16_t)0;
+        }
+        uint16_t *dst = v_pool + tile + (int64_t)d * kBlock + 4 * g;
+        if (have[0] && have[1] && have[2] && have[3]) {
+            *reinterpret_cast<u32x2 *>(dst) = u32x2{(uint32_t)val[0] | ((uint32_t)val[1] << 16), (uint32_t)val[2] | ((uint32_t)val[3] << 16)};
+        } else {
+#pragma unroll
+            for (int e = 0; e < 4; e++)
+                if (have[e]) dst[e] = val[e];
+        }
+    }
+    // ---- K: thread = (token, 8-element piece)
+    constexpr int CH = D / 8;
+    for (int x = tid; x < n_tok * CH; x += 4 * D) {
+        const int i = x / CH, c = x % CH;
+        const u32x4 kv = *reinterpret_cast<const u32x4 *>(k_new + ((int64_t)(row0 + i) * Hkv + h) * D + c * 8);
+        *reinterpret_cast<u32x4 *>(k_pool + tile + ((int64_t)c * kBlock + tok0 + i) * 8) = kv;
     }
 }
 
@@ -606,16 +623,15 @@ void free_plan_device(tc_plan *p) {
 }
 
 int launch_kv_append(const tc_plan *p, const tc_kv_pool *pool, const void *k_new, const void *v_new, void *stream) {
-    if (p->T == 0) return 0;
-    const int64_t total = (int64_t)p->T * p->Hkv * (p->D / 8);
-    const unsigned blocks = (unsigned)((total + 255) / 256);
+    if (p->n_append == 0) return 0;
     hipStream_t st = (hipStream_t)stream;
+    const dim3 grid((unsigned)p->n_append, (unsigned)p->Hkv);  // Hkv <= 1024 is checked when the plan is built
     if (p->D == 128)
-        kv_append_kernel<128><<<blocks, 256, 0, st>>>((uint16_t *)pool->k_pool, (uint16_t *)pool->v_pool, (const uint16_t *)k_new,
-                                                     (const uint16_t *)v_new, p->dev + p->off_slot, p->T, p->Hkv);
+        kv_append_kernel<128><<<grid, 512, 0, st>>>((uint16_t *)pool->k_pool, (uint16_t *)pool->v_pool, (const uint16_t *)k_new,
+                                                   (const uint16_t *)v_new, p->dev + p->off_append, p->Hkv);
     else
-        kv_append_kernel<64><<<blocks, 256, 0, st>>>((uint16_t *)pool->k_pool, (uint16_t *)pool->v_pool, (const uint16_t *)k_new,
-                                                    (const uint16_t *)v_new, p->dev + p->off_slot, p->T, p->Hkv);
+        kv_append_kernel<64><<<grid, 256, 0, st>>>((uint16_t *)pool->k_pool, (uint16_t *)pool->v_pool, (const uint16_t *)k_new,
+                                                  (const uint16_t *)v_new, p->dev + p->off_append, p->Hkv);
     return (int)hipGetLastError();
 }
 

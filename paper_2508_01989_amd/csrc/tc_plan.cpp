@@ -44,6 +44,7 @@ tc_status build_plan(const tc_kv_pool *pool, const tc_batch *b, tc_plan **out) {
     if (pool->block_size != kBlock) return fail(TC_ERR_SHAPE, "block_size must be 16");
     if (D != 64 && D != 128) return fail(TC_ERR_SHAPE, "head_dim must be 64 or 128");
     if (Hkv <= 0 || Hq <= 0 || Hq % Hkv) return fail(TC_ERR_SHAPE, "num_q_heads must be a positive multiple of num_kv_heads");
+    if (Hkv > 1024) return fail(TC_ERR_SHAPE, "more than 1024 KV heads is not supported");
     const int G = Hq / Hkv;
     if (G > 16) return fail(TC_ERR_SHAPE, "more than 16 query heads per KV head is not supported");
     if (pool->num_blocks <= 0 || pool->num_blocks * kBlock >= (int64_t)1 << 31)
@@ -97,8 +98,15 @@ tc_status build_plan(const tc_kv_pool *pool, const tc_batch *b, tc_plan **out) {
     if (n_prefill + n_decode >= ((int64_t)1 << 28)) { delete p; return fail(TC_ERR_SPAN, "batch too large"); }
     p->n_prefill = (int)n_prefill; p->n_decode = (int)n_decode; p->n_merge = (int)n_merge; p->n_partials = (int)n_partials;
 
-    p->off_slot = 0;
-    p->off_pages = p->off_slot + (size_t)p->T;
+    // append segments: the rows a sequence adds to one page (1..16 consecutive token indices)
+    int64_t n_append = 0;
+    for (int s = 0; s < S; s++) {
+        const int64_t first = p->ctx_len[s], last = first + (p->q_start[s + 1] - p->q_start[s]) - 1;
+        n_append += last / kBlock - first / kBlock + 1;
+    }
+    p->n_append = (int)n_append;
+    p->off_append = 0;
+    p->off_pages = p->off_append + (size_t)n_append * kAppendInts;
     p->off_prefill = p->off_pages + (size_t)pages;
     p->off_decode = p->off_prefill + (size_t)n_prefill * kItemInts;
     p->off_merge = p->off_decode + (size_t)n_decode * kItemInts;
@@ -115,10 +123,21 @@ tc_status build_plan(const tc_kv_pool *pool, const tc_batch *b, tc_plan **out) {
             if (row[i] < 0 || row[i] >= pool->num_blocks) { delete p; return fail(TC_ERR_BLOCK, "block table entry outside the pool"); }
             dst[i] = row[i];
         }
-        const int q = p->q_start[s + 1] - p->q_start[s];
-        for (int i = 0; i < q; i++) {
-            const int64_t pos = (int64_t)p->ctx_len[s] + i;
-            H[p->off_slot + p->q_start[s] + i] = (int32_t)((int64_t)dst[pos / kBlock] * kBlock + pos % kBlock);
+    }
+    {
+        int32_t *ap = H + p->off_append;
+        for (int s = 0; s < S; s++) {
+            const int32_t *ids = H + p->off_pages + p->page_off[s];
+            const int q = p->q_start[s + 1] - p->q_start[s];
+            int i = 0;
+            while (i < q) {
+                const int64_t pos = (int64_t)p->ctx_len[s] + i;
+                const int tok0 = (int)(pos % kBlock);
+                const int n_tok = std::min(kBlock - tok0, q - i);
+                ap[0] = p->q_start[s] + i; ap[1] = n_tok; ap[2] = tok0; ap[3] = ids[pos / kBlock];
+                ap += kAppendInts;
+                i += n_tok;
+            }
         }
     }
 
