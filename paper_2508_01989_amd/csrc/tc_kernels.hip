@@ -572,33 +572,65 @@ __global__ void __launch_bounds__(kWgThreads, kWgPerCu)
 
 // ------------------------------------------------------------------------------------
 // Split-KV merge: out = sum_i 2^(m_i - m*) o_i / sum_i 2^(m_i - m*) l_i, splits in index order.
-// One workgroup per (sequence, KV head); one thread per (head, 4 head-dim elements).
-// ------------------------------------------------------------------------------------
+// One workgroup per (sequence, KV head); one wavefront per query head; a lane owns D/64 adjacent
+// head-dim elements, so each partial row is one coalesced read.  Lane i first fetches (m_i, l_i) of
+// split i (at most 64 splits per wave pass), the wave reduces the maximum, and the weighted sum runs
+// over the splits with the weights broadcast from those registers.
 template <int D>
 __global__ void __launch_bounds__(256) split_merge_kernel(const int32_t *__restrict__ items, const float *__restrict__ ws_o,
                                                           const float *__restrict__ ws_ml, uint16_t *__restrict__ out,
                                                           int Hq, int G) {
+    constexpr int E = D / 64;  // elements per lane
     const int32_t *it = items + (int64_t)blockIdx.x * kItemInts;
     const int kvh = it[MG_KVH], qrow = it[MG_QROW], slot0 = it[MG_SLOT0], ns = it[MG_NSPLIT];
-    constexpr int QD = D / 4;
-    for (int x = threadIdx.x; x < G * QD; x += blockDim.x) {
-        const int j = x / QD, d4 = x % QD;
-        float m_star = -1e30f;
-        for (int i = 0; i < ns; i++) m_star = fmaxf(m_star, ws_ml[((int64_t)(slot0 + i) * G + j) * 2]);
-        f32x4 acc = {0.f, 0.f, 0.f, 0.f};
-        float den = 0.f;
-        for (int i = 0; i < ns; i++) {
-            const int64_t row = (int64_t)(slot0 + i) * G + j;
-            const float w = fast_exp2(ws_ml[row * 2] - m_star);
-            den += w * ws_ml[row * 2 + 1];
-            const f32x4 oi = *reinterpret_cast<const f32x4 *>(ws_o + row * D + d4 * 4);
-            acc += oi * w;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    for (int j = wave; j < G; j += 4) {
+        float acc[E];
+#pragma unroll
+        for (int e = 0; e < E; e++) acc[e] = 0.f;
+        float m_star = -1e30f, den = 0.f;
+        for (int base = 0; base < ns; base += 64) {  // 64 splits per pass; passes chained by an online rescale
+            const int n = min(64, ns - base);
+            const int64_t my_row = (int64_t)(slot0 + base + min(lane, n - 1)) * G + j;
+            const float m_i = lane < n ? ws_ml[my_row * 2] : -1e30f;
+            const float l_i = lane < n ? ws_ml[my_row * 2 + 1] : 0.f;
+            float m_new = m_i;
+#pragma unroll
+            for (int sh = 1; sh < 64; sh *= 2) m_new = fmaxf(m_new, xor_lanes(m_new, sh));
+            m_new = fmaxf(m_new, m_star);
+            const float rescale = fast_exp2(m_star - m_new);
+            m_star = m_new;
+            const float w_i = fast_exp2(m_i - m_star);  // 0 for lanes past n
+            float wl = w_i * l_i;
+#pragma unroll
+            for (int sh = 1; sh < 64; sh *= 2) wl += xor_lanes(wl, sh);
+            den = den * rescale + wl;
+#pragma unroll
+            for (int e = 0; e < E; e++) acc[e] *= rescale;
+            const float *src = ws_o + ((int64_t)(slot0 + base) * G + j) * D + lane * E;
+            for (int i = 0; i < n; i++) {
+                const float w = __shfl(w_i, i, 64);
+                if (E == 2) {
+                    const float2 v = *reinterpret_cast<const float2 *>(src + (int64_t)i * G * D);
+                    acc[0] += w * v.x;
+                    acc[E - 1] += w * v.y;
+                } else {
+                    acc[0] += w * src[(int64_t)i * G * D];
+                }
+            }
         }
         const float inv = 1.f / den;
-        bf16x4 w4;
-#pragma unroll
-        for (int e = 0; e < 4; e++) w4[e] = (__bf16)(acc[e] * inv);
-        *reinterpret_cast<bf16x4 *>(out + ((int64_t)qrow * Hq + kvh * G + j) * D + d4 * 4) = w4;
+        uint16_t *dst = out + ((int64_t)qrow * Hq + kvh * G + j) * D + lane * E;
+        if (E == 2) {
+            typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+            bf16x2 w2;
+            w2[0] = (__bf16)(acc[0] * inv);
+            w2[1] = (__bf16)(acc[E - 1] * inv);
+            *reinterpret_cast<bf16x2 *>(dst) = w2;
+        } else {
+            const __bf16 w1 = (__bf16)(acc[0] * inv);
+            *dst = __builtin_bit_cast(uint16_t, w1);
+        }
     }
 }
 
