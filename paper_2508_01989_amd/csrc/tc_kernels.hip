@@ -146,45 +146,51 @@ struct PrefillCfg {
     static constexpr int kTilePages = kTileTokens / kBlock;
     static constexpr int kPageBytes = kBlock * D * 2;               // one (page, KV head) tile of K or of V
     static constexpr int kTileBytes = kTilePages * kPageBytes;      // K part or V part of one LDS stage
-    static constexpr int kPieces = kTileBytes / 16 / kWgThreads;    // 16-byte pieces per thread per tensor
+    static constexpr int kRuns = kPageBytes / 1024;                 // 1 KiB wave-wide loads per page and tensor
     static constexpr int kLdsBytes = 2 * 2 * kTileBytes;            // two stages of K and V
 };
 
-// Page ids of one tile for the pieces this wave copies.  The page index is wave-uniform, so
-// these are scalar loads; they are issued one tile ahead of the data loads that need them.
-template <int D>
-__device__ __forceinline__ void prefill_page_ids(const int32_t *__restrict__ pages, int n_pages, int tile, int wave,
-                                                 int (&ids)[PrefillCfg<D>::kPieces]) {
-    using C = PrefillCfg<D>;
-    constexpr int kPiecesPerPage = C::kPageBytes / 16;
-#pragma unroll
-    for (int i = 0; i < C::kPieces; i++) {
-        const int b = (wave * 64 + i * kWgThreads) / kPiecesPerPage;
-        ids[i] = pages[min(tile * C::kTilePages + b, n_pages - 1)];
-    }
+// N direct-to-LDS loads of 1 KiB each (16 bytes per lane) at immediate offsets 0, 1024, ...
+template <int N>
+__device__ __forceinline__ void lds_load_runs(const __attribute__((address_space(1))) void *src,
+                                              __attribute__((address_space(3))) void *dst) {
+    static_assert(N >= 1 && N <= 4, "the immediate offset field holds up to 4095");
+    __builtin_amdgcn_global_load_lds(src, dst, 16, 0, 0);
+    if constexpr (N > 1) __builtin_amdgcn_global_load_lds(src, dst, 16, 1024, 0);
+    if constexpr (N > 2) __builtin_amdgcn_global_load_lds(src, dst, 16, 2048, 0);
+    if constexpr (N > 3) __builtin_amdgcn_global_load_lds(src, dst, 16, 3072, 0);
 }
 
-// Copy one K/V tile (four pages of one KV head) from the pool straight into an LDS stage with
-// direct-to-LDS loads: lane L of a wave deposits its 16 bytes at (wave-uniform base) + 16 L, so
-// each wave copies 1 KiB runs.  K pages are copied verbatim.  A V^T page is copied row by row
-// (32 bytes = 16 token slots of one head-dim element) with the two 16-byte halves of rows 8-15
-// (mod 16) exchanged, so that the operand reads of 16 consecutive rows cover all 64 LDS banks.
+// Tile copies: wave w of the workgroup copies page w of the tile (kWgWaves == pages per tile).
+// Page id of the page this wave copies (a scalar load, issued one tile ahead of its use).
 template <int D>
-__device__ __forceinline__ void prefill_fetch(const AttnArgs &A, int kvh, const int (&ids)[PrefillCfg<D>::kPieces],
-                                              char *lds_k, char *lds_v, int wave, int lane) {
+__device__ __forceinline__ int prefill_page_id(const int32_t *__restrict__ pages, int n_pages, int tile, int wave) {
+    return pages[min(tile * PrefillCfg<D>::kTilePages + wave, n_pages - 1)];
+}
+
+// Copy one page of K and of V^T (one KV head) from the pool straight into an LDS stage with
+// direct-to-LDS loads: lane L deposits its 16 bytes at (wave-uniform base) + 16 L, so each load
+// copies a 1 KiB run; the runs of a page are contiguous both in the pool and in LDS, so they share
+// one address register and one LDS base and differ only in the instruction's immediate offset.
+// K pages are copied verbatim.  A V^T page is copied row by row (32 bytes = 16 token slots of one
+// head-dim element) with the two 16-byte halves of rows 8-15 (mod 16) exchanged, so that the
+// operand reads of 16 consecutive rows cover all 64 LDS banks (a 1 KiB step is 32 rows, so the
+// exchange pattern is the same in every run).
+template <int D>
+__device__ __forceinline__ void prefill_fetch(const AttnArgs &A, int kvh, int page_id, char *lds_k, char *lds_v, int wave,
+                                              int lane) {
     using C = PrefillCfg<D>;
-    constexpr int kPiecesPerPage = C::kPageBytes / 16;
+    static_assert(C::kTilePages == kWgWaves, "one wave per page of a tile");
     typedef const __attribute__((address_space(1))) void *gptr_t;
     typedef __attribute__((address_space(3))) void *lptr_t;
-#pragma unroll
-    for (int i = 0; i < C::kPieces; i++) {
-        const int x0 = wave * 64 + i * kWgThreads;  // first 16-byte piece of this wave's run
-        const int off = x0 % kPiecesPerPage + lane;
-        const int64_t base = ((int64_t)__builtin_amdgcn_readfirstlane(ids[i]) * A.Hkv + kvh) * (int64_t)(kBlock * D);
-        const int d = off >> 1, half = (off & 1) ^ ((d >> 3) & 1);
-        __builtin_amdgcn_global_load_lds((gptr_t)(A.k_pool + base + off * 8), (lptr_t)(lds_k + x0 * 16), 16, 0, 0);
-        __builtin_amdgcn_global_load_lds((gptr_t)(A.v_pool + base + d * kBlock + half * 8), (lptr_t)(lds_v + x0 * 16), 16, 0, 0);
-    }
+    const int64_t base = ((int64_t)__builtin_amdgcn_readfirstlane(page_id) * A.Hkv + kvh) * (int64_t)(kBlock * D);
+    const int d = lane >> 1, half = (lane & 1) ^ ((d >> 3) & 1);
+    const gptr_t ksrc = (gptr_t)(A.k_pool + base + lane * 8);
+    const gptr_t vsrc = (gptr_t)(A.v_pool + base + d * kBlock + half * 8);
+    const lptr_t kdst = (lptr_t)(lds_k + wave * C::kPageBytes);
+    const lptr_t vdst = (lptr_t)(lds_v + wave * C::kPageBytes);
+    lds_load_runs<C::kRuns>(ksrc, kdst);
+    lds_load_runs<C::kRuns>(vsrc, vdst);
 }
 
 // After this thread's own direct-to-LDS loads of `tile` have landed: slots at or past `kv_len`
@@ -194,15 +200,12 @@ __device__ __forceinline__ void prefill_fetch(const AttnArgs &A, int kvh, const 
 template <int D>
 __device__ __forceinline__ void prefill_fix_tail(char *lds_v, int tile, int wave, int lane, int kv_len) {
     using C = PrefillCfg<D>;
-    constexpr int kPiecesPerPage = C::kPageBytes / 16;
+    const int n_valid = kv_len - (tile * C::kTilePages + wave) * kBlock;
+    if (n_valid < kBlock) {
+        const int d = lane >> 1, half = (lane & 1) ^ ((d >> 3) & 1);
 #pragma unroll
-    for (int i = 0; i < C::kPieces; i++) {
-        const int x0 = wave * 64 + i * kWgThreads;
-        const int n_valid = kv_len - (tile * C::kTilePages + x0 / kPiecesPerPage) * kBlock;
-        if (n_valid < kBlock) {
-            const int off = x0 % kPiecesPerPage + lane;
-            const int d = off >> 1, half = (off & 1) ^ ((d >> 3) & 1);
-            u32x4 *piece = reinterpret_cast<u32x4 *>(lds_v + (x0 + lane) * 16);
+        for (int i = 0; i < C::kRuns; i++) {
+            u32x4 *piece = reinterpret_cast<u32x4 *>(lds_v + wave * C::kPageBytes + i * 1024 + lane * 16);
             u32x4 vv = *piece;
 #pragma unroll
             for (int e = 0; e < 4; e++) {
@@ -275,10 +278,9 @@ __device__ void prefill_item(const AttnArgs &A, const int32_t *__restrict__ it, 
 #pragma unroll
     for (int e = 0; e < 8; e++) ones[e] = (__bf16)1.0f;
 
-    int ids[C::kPieces];
-    prefill_page_ids<D>(pages, n_pages, 0, wave, ids);
-    prefill_fetch<D>(A, kvh, ids, lds, lds + 2 * C::kTileBytes, wave, lane);
-    prefill_page_ids<D>(pages, n_pages, 1, wave, ids);
+    int page_id = prefill_page_id<D>(pages, n_pages, 0, wave);
+    prefill_fetch<D>(A, kvh, page_id, lds, lds + 2 * C::kTileBytes, wave, lane);
+    page_id = prefill_page_id<D>(pages, n_pages, 1, wave);
     wait_all_loads();
     if (kv_len < C::kTileTokens) prefill_fix_tail<D>(lds + 2 * C::kTileBytes, 0, wave, lane, kv_len);
     __syncthreads();
@@ -289,8 +291,8 @@ __device__ void prefill_item(const AttnArgs &A, const int32_t *__restrict__ it, 
         const char *vs = lds + 2 * C::kTileBytes + cur * C::kTileBytes;
         const bool more = tile + 1 < n_tiles;
         if (more) {  // stage cur^1 was last read before the barrier that ended the previous iteration
-            prefill_fetch<D>(A, kvh, ids, lds + (cur ^ 1) * C::kTileBytes, lds + 2 * C::kTileBytes + (cur ^ 1) * C::kTileBytes, wave, lane);
-            prefill_page_ids<D>(pages, n_pages, tile + 2, wave, ids);
+            prefill_fetch<D>(A, kvh, page_id, lds + (cur ^ 1) * C::kTileBytes, lds + 2 * C::kTileBytes + (cur ^ 1) * C::kTileBytes, wave, lane);
+            page_id = prefill_page_id<D>(pages, n_pages, tile + 2, wave);
         }
 
         const int tok0 = tile * C::kTileTokens;
