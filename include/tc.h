@@ -140,6 +140,31 @@ tc_status tc_mixed_attention(const tc_plan *plan, const tc_kv_pool *pool, const 
 tc_status tc_kv_gather(const tc_plan *plan, const tc_kv_pool *pool, int32_t seq, void *k_out, void *v_out,
                        void *stream);
 
+/*
+ * KV migration (paper Sec. 3.5 "Implementation": the KV cache of a request moves between
+ * instances, and a fused operator stores what was received into the paged memory; Sec. 3.3,
+ * flowing decode, and the prefill-to-decode hand-off of Sec. 3.4 are what trigger it).  On one
+ * GPU the move is pool -> contiguous transfer buffer (tc_kv_export) and transfer buffer -> the
+ * blocks of another table or pool (tc_kv_import), for all layers of the model in one call.
+ *
+ * `seq` selects one sequence of the plan (its tokens 0..ctx_len+q_len-1), or all of them with
+ * seq = -1, in plan order.  With P = the pages of the selection (ceil(kv_len/16) per sequence,
+ * summed) the transfer buffer is bf16 [num_layers][P][2][Hkv*16*D]: for each layer and page the
+ * K block then the V block, each in the pool's own block layout (see the top of this file), so
+ * both directions move whole 16-byte pieces.  Token slots of a sequence's last page at or
+ * beyond its length are written as zero by the export and are ignored by the import, which
+ * stores only real tokens: every other pool byte is left untouched.  Bit copy.
+ *
+ * k_pools / v_pools: HOST arrays of num_layers DEVICE pointers (the per-layer pools, all of the
+ * shape in `pool`; pool->k_pool / v_pool themselves are not used).  buffer: DEVICE,
+ * tc_kv_transfer_bytes() bytes.  1 <= num_layers <= 4096.
+ */
+size_t tc_kv_transfer_bytes(const tc_plan *plan, int32_t seq, int32_t num_layers);
+tc_status tc_kv_export(const tc_plan *plan, const tc_kv_pool *pool, int32_t seq, int32_t num_layers,
+                       const void *const *k_pools, const void *const *v_pools, void *buffer, void *stream);
+tc_status tc_kv_import(const tc_plan *plan, const tc_kv_pool *pool, int32_t seq, int32_t num_layers,
+                       void *const *k_pools, void *const *v_pools, const void *buffer, void *stream);
+
 const char *tc_status_str(tc_status s);
 /* Text of the last error raised on the calling thread ("" if none). */
 const char *tc_last_error(void);

@@ -4,7 +4,8 @@ TEST INFRASTRUCTURE: imported only by tests/, __graft_entry__.smoke() and the
 cpu_baseline leg of bench.py.  It does not import the GPU package and the GPU
 package does not import it.  Follows paper Sec. 2.1 (attention over all tokens so
 far, K/V cached), Sec. 2.2 (a chunk of a prompt at a chunk offset, decodes
-piggybacked) and Sec. 3.5 (paged KV memory); see tc_oracle.c for the formulas.
+piggybacked) and Sec. 3.5 (paged KV memory, KV migration between instances); see
+tc_oracle.c for the formulas.
 """
 from __future__ import annotations
 
@@ -27,6 +28,11 @@ def lib():
                                        u16p, u16p]
         _lib.tco_attention.argtypes = [C.c_int, C.c_int, C.c_int, C.c_int, C.c_int64, u16p, u16p, C.c_int,
                                        i32p, i32p, i32p, C.c_int, u16p, C.c_double, i32p, C.c_int64, f64p]
+        pp = C.POINTER(C.c_void_p)
+        _lib.tco_kv_export.argtypes = [C.c_int, C.c_int, C.c_int, C.c_int64, C.c_int, pp, pp, i32p, C.c_int64,
+                                       C.c_int64, C.c_int64, u16p]
+        _lib.tco_kv_import.argtypes = [C.c_int, C.c_int, C.c_int, C.c_int64, C.c_int, pp, pp, i32p, C.c_int64,
+                                       C.c_int64, C.c_int64, u16p]
         _lib.tco_num_threads.restype = C.c_int
     return _lib
 
@@ -79,6 +85,57 @@ def kv_gather(k_pool, v_pool, num_kv_heads, head_dim, block_size, table_row, kv_
     if rc:
         raise ValueError(f"oracle kv_gather: block id outside the pool (rc={rc})")
     return k, v
+
+
+def _ptr_array(pools):
+    return (C.c_void_p * len(pools))(*[a.ctypes.data for a in pools])
+
+
+def transfer_pages(kv_lens, block_size=16):
+    """Pages each sequence occupies in a transfer buffer, and their exclusive prefix sum."""
+    pages = [(int(n) + block_size - 1) // block_size for n in kv_lens]
+    return pages, np.concatenate([[0], np.cumsum(pages)]).astype(np.int64)
+
+
+def kv_export(k_pools, v_pools, num_kv_heads, head_dim, block_size, block_table, kv_lens):
+    """Pack the listed sequences (row s of block_table, kv_lens[s] tokens) of every layer's pool into
+    one transfer buffer, uint16 [L][P][2][Hkv*B*D] (per layer and page: K block, V block, in the
+    pool's block layout; slots of a last page beyond the sequence's length are zero)."""
+    table = _c(block_table, np.int32)
+    L = len(k_pools)
+    pages, off = transfer_pages(kv_lens, block_size)
+    P = int(off[-1])
+    E = num_kv_heads * block_size * head_dim
+    nb = k_pools[0].size // E
+    buf = np.full(L * P * 2 * E, 0xABCD, np.uint16)
+    kp, vp = _ptr_array(k_pools), _ptr_array(v_pools)
+    for s, n in enumerate(kv_lens):
+        row = np.ascontiguousarray(table[s])
+        rc = lib().tco_kv_export(num_kv_heads, head_dim, block_size, nb, L, kp, vp, _p(row, C.c_int32), int(n),
+                                 int(off[s]), P, _p(buf, C.c_uint16))
+        if rc:
+            raise ValueError(f"oracle kv_export: block id outside the pool (rc={rc})")
+    return buf
+
+
+def kv_import(k_pools, v_pools, num_kv_heads, head_dim, block_size, block_table, kv_lens, buf):
+    """In place: store the tokens held in a transfer buffer (see kv_export) into the blocks that
+    block_table names, for every layer's pool."""
+    table = _c(block_table, np.int32)
+    buf = _c(buf, np.uint16)
+    L = len(k_pools)
+    pages, off = transfer_pages(kv_lens, block_size)
+    P = int(off[-1])
+    E = num_kv_heads * block_size * head_dim
+    nb = k_pools[0].size // E
+    assert buf.size == L * P * 2 * E
+    kp, vp = _ptr_array(k_pools), _ptr_array(v_pools)
+    for s, n in enumerate(kv_lens):
+        row = np.ascontiguousarray(table[s])
+        rc = lib().tco_kv_import(num_kv_heads, head_dim, block_size, nb, L, kp, vp, _p(row, C.c_int32), int(n),
+                                 int(off[s]), P, _p(buf, C.c_uint16))
+        if rc:
+            raise ValueError(f"oracle kv_import: block id outside the pool (rc={rc})")
 
 
 def attention(k_pool, v_pool, num_q_heads, num_kv_heads, head_dim, block_size, q_start, ctx_len, block_table,

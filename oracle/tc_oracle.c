@@ -139,6 +139,61 @@ int tco_kv_gather(int Hkv, int D, int B, int64_t num_blocks, const uint16_t *k_p
 }
 
 /*
+ * KV migration (Sec. 3.5: a request's KV cache moves between instances and is stored into the
+ * receiver's paged memory).  The transfer buffer is [L][P][2][Hkv*B*D]: per layer and page the K
+ * block, then the V block, each in the pool's block layout.  One call handles one sequence whose
+ * pages start at page index page0 of the P pages of the buffer.
+ * Export copies tokens 0..kv_len-1 and writes zero into the token slots of the last page that are
+ * at or beyond kv_len.
+ */
+int tco_kv_export(int Hkv, int D, int B, int64_t num_blocks, int L, const uint16_t *const *k_pools,
+                  const uint16_t *const *v_pools, const int32_t *table_row, int64_t kv_len, int64_t page0,
+                  int64_t P, uint16_t *buf)
+{
+    shape_t sh = {0, Hkv, D, B, num_blocks};
+    int64_t E = (int64_t)Hkv * B * D; /* elements of one block of one pool */
+    int64_t pages = (kv_len + B - 1) / B;
+    for (int l = 0; l < L; l++)
+        for (int64_t j = 0; j < pages * B; j++) {
+            int64_t blk = table_row[j / B];
+            if (blk < 0 || blk >= num_blocks) return -1;
+            int tok = (int)(j % B);
+            uint16_t *kdst = buf + ((l * P + page0 + j / B) * 2 + 0) * E;
+            uint16_t *vdst = buf + ((l * P + page0 + j / B) * 2 + 1) * E;
+            for (int h = 0; h < Hkv; h++)
+                for (int d = 0; d < D; d++) {
+                    int real = j < kv_len;
+                    kdst[k_index(&sh, 0, h, tok, d)] = real ? k_pools[l][k_index(&sh, blk, h, tok, d)] : 0;
+                    vdst[v_index(&sh, 0, h, tok, d)] = real ? v_pools[l][v_index(&sh, blk, h, tok, d)] : 0;
+                }
+        }
+    return 0;
+}
+
+/* Import stores tokens 0..kv_len-1 of the buffer into the blocks of table_row; nothing else is written. */
+int tco_kv_import(int Hkv, int D, int B, int64_t num_blocks, int L, uint16_t *const *k_pools,
+                  uint16_t *const *v_pools, const int32_t *table_row, int64_t kv_len, int64_t page0, int64_t P,
+                  const uint16_t *buf)
+{
+    shape_t sh = {0, Hkv, D, B, num_blocks};
+    int64_t E = (int64_t)Hkv * B * D;
+    for (int l = 0; l < L; l++)
+        for (int64_t j = 0; j < kv_len; j++) {
+            int64_t blk = table_row[j / B];
+            if (blk < 0 || blk >= num_blocks) return -1;
+            int tok = (int)(j % B);
+            const uint16_t *ksrc = buf + ((l * P + page0 + j / B) * 2 + 0) * E;
+            const uint16_t *vsrc = buf + ((l * P + page0 + j / B) * 2 + 1) * E;
+            for (int h = 0; h < Hkv; h++)
+                for (int d = 0; d < D; d++) {
+                    k_pools[l][k_index(&sh, blk, h, tok, d)] = ksrc[k_index(&sh, 0, h, tok, d)];
+                    v_pools[l][v_index(&sh, blk, h, tok, d)] = vsrc[v_index(&sh, 0, h, tok, d)];
+                }
+        }
+    return 0;
+}
+
+/*
  * Attention for selected packed query rows (rows == NULL: all of them), every head.
  * out is double [n_rows][Hq][D].  Reads the pool as it stands, i.e. after the append.
  *   s_j = scale * sum_d q_d k_{j,d}   (j = 0..p, the token itself included)
