@@ -18,7 +18,7 @@ TC_BF16 = 1
 
 EXPORTS = ["tc_plan_create", "tc_plan_create_host", "tc_plan_get_info", "tc_plan_copy_items",
            "tc_plan_workspace_bytes", "tc_plan_destroy", "tc_kv_append", "tc_mixed_attention", "tc_kv_gather",
-           "tc_status_str", "tc_last_error", "tc_version"]
+           "tc_kv_transfer_bytes", "tc_kv_export", "tc_kv_import", "tc_status_str", "tc_last_error", "tc_version"]
 
 
 class tc_kv_pool(C.Structure):
@@ -68,6 +68,10 @@ def lib():
         L.tc_kv_append.argtypes = [vp, C.POINTER(tc_kv_pool), vp, vp, vp]
         L.tc_mixed_attention.argtypes = [vp, C.POINTER(tc_kv_pool), vp, vp, C.c_float, vp, C.c_size_t, vp]
         L.tc_kv_gather.argtypes = [vp, C.POINTER(tc_kv_pool), C.c_int32, vp, vp, vp]
+        L.tc_kv_transfer_bytes.argtypes = [vp, C.c_int32, C.c_int32]
+        L.tc_kv_transfer_bytes.restype = C.c_size_t
+        L.tc_kv_export.argtypes = [vp, C.POINTER(tc_kv_pool), C.c_int32, C.c_int32, C.POINTER(vp), C.POINTER(vp), vp, vp]
+        L.tc_kv_import.argtypes = [vp, C.POINTER(tc_kv_pool), C.c_int32, C.c_int32, C.POINTER(vp), C.POINTER(vp), vp, vp]
         L.tc_status_str.argtypes = [C.c_int]
         L.tc_status_str.restype = C.c_char_p
         L.tc_last_error.restype = C.c_char_p
@@ -168,6 +172,29 @@ def tc_mixed_attention(plan: Plan, pool: tc_kv_pool, q, out, scale, workspace=No
 
 def tc_kv_gather(plan: Plan, pool: tc_kv_pool, seq, k_out, v_out, stream=None):
     _check(lib().tc_kv_gather(plan.handle, C.byref(pool), int(seq), _ptr(k_out), _ptr(v_out), _stream(stream)))
+
+
+def _ptr_array(pools):
+    """HOST array of the device addresses of the per-layer pools."""
+    if pools is None:
+        return None
+    return (C.c_void_p * len(pools))(*[_ptr(x) for x in pools])
+
+
+def tc_kv_transfer_bytes(plan: Plan, seq: int, num_layers: int) -> int:
+    return int(lib().tc_kv_transfer_bytes(plan.handle, int(seq), int(num_layers)))
+
+
+def tc_kv_export(plan: Plan, pool: tc_kv_pool, seq, k_pools, v_pools, buffer, num_layers=None, stream=None):
+    n = len(k_pools) if num_layers is None else num_layers
+    _check(lib().tc_kv_export(plan.handle, C.byref(pool), int(seq), int(n), _ptr_array(k_pools), _ptr_array(v_pools),
+                              _ptr(buffer), _stream(stream)))
+
+
+def tc_kv_import(plan: Plan, pool: tc_kv_pool, seq, k_pools, v_pools, buffer, num_layers=None, stream=None):
+    n = len(k_pools) if num_layers is None else num_layers
+    _check(lib().tc_kv_import(plan.handle, C.byref(pool), int(seq), int(n), _ptr_array(k_pools), _ptr_array(v_pools),
+                              _ptr(buffer), _stream(stream)))
 
 
 def tc_version() -> int:

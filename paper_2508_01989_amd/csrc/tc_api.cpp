@@ -56,3 +56,52 @@ tc_status tc_kv_gather(const tc_plan *plan, const tc_kv_pool *pool, int32_t seq,
 }
 
 }  // extern "C"
+
+namespace {
+
+// Pages [page0, page0 + n) of the plan that `seq` selects (-1 = every sequence).
+bool selection(const tc_plan *plan, int32_t seq, int *page0, int *n) {
+    if (seq == -1) { *page0 = 0; *n = (int)plan->total_pages; return true; }
+    if (seq < 0 || seq >= plan->S) return false;
+    *page0 = plan->page_off[seq];
+    *n = plan->page_off[seq + 1] - plan->page_off[seq];
+    return true;
+}
+
+tc_status migrate(const tc_plan *plan, const tc_kv_pool *pool, int32_t seq, int32_t num_layers, void *const *k_pools,
+                  void *const *v_pools, void *buffer, void *stream, bool import) {
+    tc_status st = tc::check_pool_matches(plan, pool, false);
+    if (st != TC_OK) return st;
+    if (!plan->dev) return fail(TC_ERR_ARG, "plan was built host-only (tc_plan_create_host) and cannot be launched");
+    int page0 = 0, n = 0;
+    if (!selection(plan, seq, &page0, &n)) return fail(TC_ERR_ARG, "sequence index out of range");
+    if (num_layers < 1 || num_layers > tc::kMaxLayers) return fail(TC_ERR_ARG, "num_layers must be in [1, 4096]");
+    if (n == 0) return TC_OK;
+    if (!k_pools || !v_pools || !buffer) return fail(TC_ERR_NULL, "k_pools, v_pools or buffer is NULL");
+    for (int l = 0; l < num_layers; l++)
+        if (!k_pools[l] || !v_pools[l]) return fail(TC_ERR_NULL, "a layer's pool pointer is NULL");
+    return device_result(tc::launch_kv_migrate(plan, import, page0, n, num_layers, k_pools, v_pools, buffer, stream),
+                         import ? "tc_kv_import launch" : "tc_kv_export launch");
+}
+
+}  // namespace
+
+extern "C" {
+
+size_t tc_kv_transfer_bytes(const tc_plan *plan, int32_t seq, int32_t num_layers) {
+    int page0 = 0, n = 0;
+    if (!plan || num_layers < 1 || num_layers > tc::kMaxLayers || !selection(plan, seq, &page0, &n)) return 0;
+    return (size_t)num_layers * (size_t)n * 2 * (size_t)plan->Hkv * tc::kBlock * (size_t)plan->D * sizeof(uint16_t);
+}
+
+tc_status tc_kv_export(const tc_plan *plan, const tc_kv_pool *pool, int32_t seq, int32_t num_layers,
+                       const void *const *k_pools, const void *const *v_pools, void *buffer, void *stream) {
+    return migrate(plan, pool, seq, num_layers, (void *const *)k_pools, (void *const *)v_pools, buffer, stream, false);
+}
+
+tc_status tc_kv_import(const tc_plan *plan, const tc_kv_pool *pool, int32_t seq, int32_t num_layers,
+                       void *const *k_pools, void *const *v_pools, const void *buffer, void *stream) {
+    return migrate(plan, pool, seq, num_layers, k_pools, v_pools, (void *)buffer, stream, true);
+}
+
+}  // extern "C"

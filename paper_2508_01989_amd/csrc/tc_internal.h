@@ -18,6 +18,8 @@ constexpr int kPrefillRows = 32 * kWgWaves;  // (position, head) rows per prefil
 constexpr int kItemInts = 8;        // int32 fields per work item
 constexpr int kAppendInts = 4;      // int32 fields per append segment: first packed row, tokens, first token index, pool block
 constexpr int kMaxSplitPages = 64;  // a decode split's page ids fit one wavefront register
+constexpr int kMigrateLayers = 64;  // layers one migration launch covers (their pool pointers travel as kernel arguments)
+constexpr int kMaxLayers = 4096;
 
 // Field indices of work items (see tc_plan_copy_items in tc.h).
 enum { PF_SEQ, PF_KVH, PF_POS0, PF_NPOS, PF_QROW0, PF_CTX, PF_PAGEOFF, PF_NPAGES };
@@ -39,7 +41,7 @@ struct tc_plan {
     std::vector<int32_t> q_start, ctx_len, page_off;  // host copies
     // One int32 buffer uploaded as a whole; offsets (in int32 units) of its sections.
     std::vector<int32_t> host;
-    size_t off_append = 0, off_pages = 0, off_prefill = 0, off_decode = 0, off_merge = 0;
+    size_t off_append = 0, off_pages = 0, off_valid = 0, off_prefill = 0, off_decode = 0, off_merge = 0;  // off_valid: tokens (1..16) each page holds
     int n_append = 0;  // (sequence, page) segments written by the append
     int32_t *dev = nullptr;  // device copy of `host`, nullptr for host-only plans
     int device = -1;
@@ -62,6 +64,9 @@ int launch_kv_append(const tc_plan *p, const tc_kv_pool *pool, const void *k_new
 int launch_kv_gather(const tc_plan *p, const tc_kv_pool *pool, int seq, void *k_out, void *v_out, void *stream);
 int launch_attention(const tc_plan *p, const tc_kv_pool *pool, const void *q, void *out, float scale,
                      void *workspace, void *stream);
+// Pool <-> transfer buffer copy of the pages [page0, page0 + n_pages) of the plan, all layers.
+int launch_kv_migrate(const tc_plan *p, bool import, int page0, int n_pages, int num_layers, void *const *k_pools,
+                      void *const *v_pools, void *buffer, void *stream);
 int upload_plan(tc_plan *p, void *stream);
 void free_plan_device(tc_plan *p);
 const char *hip_error_text(int err);

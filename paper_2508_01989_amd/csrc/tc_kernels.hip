@@ -2,6 +2,7 @@
 //
 //   kv_append_kernel   scatter this iteration's K/V rows into the paged pools      (HBM-bound)
 //   kv_gather_kernel   un-paged copy of one sequence (test hook)                   (HBM-bound)
+//   kv_migrate_kernel  pool <-> contiguous transfer buffer, all layers (paper Sec. 3.5)   (HBM-bound)
 //   mixed_attention_kernel  ONE launch per layer for the whole mixed batch
 //       (paper Sec. 2.2: a prompt chunk plus piggybacked decodes share an iteration):
 //         workgroups [0, n_prefill)      causal chunked-prefill tiles, MFMA 32x32x16 bf16
@@ -127,6 +128,84 @@ __global__ void __launch_bounds__(256) kv_gather_kernel(const uint16_t *__restri
 #pragma unroll
     for (int e = 0; e < 4; e++) vv[e] = (uint32_t)vsrc[(2 * e) * kBlock] | ((uint32_t)vsrc[(2 * e + 1) * kBlock] << 16);
     *reinterpret_cast<u32x4 *>(v_out + dst) = vv;
+}
+
+// ------------------------------------------------------------------------------------
+// KV migration: pool <-> contiguous transfer buffer, every layer in one launch
+// ------------------------------------------------------------------------------------
+// The transfer buffer is [layers][pages][K block | V block] with both blocks in the pool's own
+// layout, so a page moves as 16-byte pieces that are contiguous on both sides; the block id is
+// the only indirection.  Workgroup (x, y) moves page x of the selection for layer y.  A full page
+// is a straight copy with eight loads in flight per thread.  The last page of a sequence may hold
+// fewer than 16 tokens: the export writes zero for the missing ones, the import stores only the
+// real ones (K: 16-byte pieces of real tokens; V, which is token-minor: 2-byte elements).
+struct MigratePools {
+    uint16_t *k[kMigrateLayers];
+    uint16_t *v[kMigrateLayers];
+};
+
+template <bool IMPORT>
+__global__ void __launch_bounds__(256) kv_migrate_kernel(const MigratePools pools, const int32_t *__restrict__ pages,
+                                                         const int32_t *__restrict__ valid, uint16_t *__restrict__ buffer,
+                                                         int64_t layer_stride, int block_pieces) {
+    const int page = blockIdx.x, layer = blockIdx.y;
+    const int64_t blk = pages[page];
+    const int n_valid = valid[page];
+    const int64_t E = (int64_t)block_pieces * 8;  // elements of one block of one pool
+    u32x4 *kb = reinterpret_cast<u32x4 *>(buffer + (int64_t)layer * layer_stride + (int64_t)page * 2 * E);
+    u32x4 *vb = kb + block_pieces;
+    u32x4 *kp = reinterpret_cast<u32x4 *>(pools.k[layer] + blk * E);
+    u32x4 *vp = reinterpret_cast<u32x4 *>(pools.v[layer] + blk * E);
+    const int tid = threadIdx.x;
+    if (n_valid == kBlock) {
+        const u32x4 *src_k = IMPORT ? kb : kp, *src_v = IMPORT ? vb : vp;
+        u32x4 *dst_k = IMPORT ? kp : kb, *dst_v = IMPORT ? vp : vb;
+        constexpr int U = 4;  // pieces of each tensor in flight per thread
+        for (int x0 = tid; x0 < block_pieces; x0 += 256 * U) {
+            u32x4 a[U], b[U];
+#pragma unroll
+            for (int u = 0; u < U; u++) {
+                const int x = x0 + 256 * u;
+                if (x < block_pieces) {
+                    a[u] = __builtin_nontemporal_load(src_k + x);
+                    b[u] = __builtin_nontemporal_load(src_v + x);
+                }
+            }
+#pragma unroll
+            for (int u = 0; u < U; u++) {
+                const int x = x0 + 256 * u;
+                if (x < block_pieces) {
+                    __builtin_nontemporal_store(a[u], dst_k + x);
+                    __builtin_nontemporal_store(b[u], dst_v + x);
+                }
+            }
+        }
+        return;
+    }
+    for (int x = tid; x < block_pieces; x += 256) {
+        // K piece x = (head, d/8, token): the token index is the piece index mod 16
+        const bool real = (x & (kBlock - 1)) < n_valid;
+        if (IMPORT) {
+            if (real) kp[x] = kb[x];
+        } else {
+            kb[x] = real ? kp[x] : u32x4{0u, 0u, 0u, 0u};
+        }
+        // V piece x = (head, d, half row): slots 8*(x&1) .. +7, slot s holds token v_slot(s)
+        const int slot0 = (x & 1) * 8;
+        if (IMPORT) {
+            const u32x4 w = vb[x];
+            uint16_t *dst = reinterpret_cast<uint16_t *>(vp + x);
+#pragma unroll
+            for (int e = 0; e < 8; e++)
+                if (v_slot(slot0 + e) < n_valid) dst[e] = (uint16_t)(w[e >> 1] >> ((e & 1) * 16));
+        } else {
+            u32x4 w = vp[x];
+#pragma unroll
+            for (int e = 0; e < 8; e++)
+                if (v_slot(slot0 + e) >= n_valid) w[e >> 1] &= (e & 1) ? 0x0000FFFFu : 0xFFFF0000u;
+            vb[x] = w;
+        }
+    }
 }
 
 // ------------------------------------------------------------------------------------
@@ -682,6 +761,32 @@ int launch_kv_gather(const tc_plan *p, const tc_kv_pool *pool, int seq, void *k_
         kv_gather_kernel<64><<<blocks, 256, 0, st>>>((const uint16_t *)pool->k_pool, (const uint16_t *)pool->v_pool, pages, kv_len,
                                                     p->Hkv, (uint16_t *)k_out, (uint16_t *)v_out);
     return (int)hipGetLastError();
+}
+
+int launch_kv_migrate(const tc_plan *p, bool import, int page0, int n_pages, int num_layers, void *const *k_pools,
+                      void *const *v_pools, void *buffer, void *stream) {
+    if (n_pages == 0) return 0;
+    hipStream_t st = (hipStream_t)stream;
+    const int block_pieces = p->Hkv * p->D * 2;  // 16-byte pieces of one block of one pool
+    const int64_t layer_stride = (int64_t)n_pages * 2 * block_pieces * 8;  // buffer elements per layer
+    const int32_t *pages = p->dev + p->off_pages + page0, *valid = p->dev + p->off_valid + page0;
+    for (int l0 = 0; l0 < num_layers; l0 += kMigrateLayers) {
+        const int nl = std::min(kMigrateLayers, num_layers - l0);
+        MigratePools mp;
+        for (int l = 0; l < kMigrateLayers; l++) {
+            mp.k[l] = (uint16_t *)k_pools[l0 + std::min(l, nl - 1)];
+            mp.v[l] = (uint16_t *)v_pools[l0 + std::min(l, nl - 1)];
+        }
+        uint16_t *buf = (uint16_t *)buffer + (int64_t)l0 * layer_stride;
+        const dim3 grid((unsigned)n_pages, (unsigned)nl);
+        if (import)
+            kv_migrate_kernel<true><<<grid, 256, 0, st>>>(mp, pages, valid, buf, layer_stride, block_pieces);
+        else
+            kv_migrate_kernel<false><<<grid, 256, 0, st>>>(mp, pages, valid, buf, layer_stride, block_pieces);
+        hipError_t e = hipGetLastError();
+        if (e != hipSuccess) return (int)e;
+    }
+    return 0;
 }
 
 template <int D>

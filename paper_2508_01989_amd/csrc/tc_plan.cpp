@@ -107,7 +107,8 @@ tc_status build_plan(const tc_kv_pool *pool, const tc_batch *b, tc_plan **out) {
     p->n_append = (int)n_append;
     p->off_append = 0;
     p->off_pages = p->off_append + (size_t)n_append * kAppendInts;
-    p->off_prefill = p->off_pages + (size_t)pages;
+    p->off_valid = p->off_pages + (size_t)pages;
+    p->off_prefill = p->off_valid + (size_t)pages;
     p->off_decode = p->off_prefill + (size_t)n_prefill * kItemInts;
     p->off_merge = p->off_decode + (size_t)n_decode * kItemInts;
     const size_t total = p->off_merge + (size_t)n_merge * kItemInts;
@@ -123,6 +124,10 @@ tc_status build_plan(const tc_kv_pool *pool, const tc_batch *b, tc_plan **out) {
             if (row[i] < 0 || row[i] >= pool->num_blocks) { delete p; return fail(TC_ERR_BLOCK, "block table entry outside the pool"); }
             dst[i] = row[i];
         }
+        // tokens held by each page: 16, except the last page of the sequence
+        const int kv = p->ctx_len[s] + (p->q_start[s + 1] - p->q_start[s]);
+        int32_t *val = H + p->off_valid + p->page_off[s];
+        for (int i = 0; i < np; i++) val[i] = std::min(kBlock, kv - i * kBlock);
     }
     {
         int32_t *ap = H + p->off_append;

@@ -101,6 +101,22 @@ def test_host_only_plan_cannot_be_launched(tc):
     assert _status(tc, lambda: tc.tc_kv_append(p, pool3, 4096, 4096)) == tc.TC_ERR_NULL
 
 
+def test_migration_argument_checks_and_buffer_size(tc):
+    p = _plan(tc)  # sequences of 8 and 41 tokens: 1 and 3 pages; Hkv=2, D=128 -> 8 KiB per block per pool
+    per_page = 2 * 2 * 16 * 128 * 2
+    assert tc.tc_kv_transfer_bytes(p, 0, 1) == 1 * per_page
+    assert tc.tc_kv_transfer_bytes(p, 1, 5) == 5 * 3 * per_page
+    assert tc.tc_kv_transfer_bytes(p, -1, 2) == 2 * 4 * per_page
+    assert tc.tc_kv_transfer_bytes(p, 2, 1) == 0 and tc.tc_kv_transfer_bytes(p, -2, 1) == 0
+    assert tc.tc_kv_transfer_bytes(p, 0, 0) == 0 and tc.tc_kv_transfer_bytes(p, 0, 4097) == 0
+    pool = tc.make_pool(8, 2, 128, 32)
+    # a host-only plan cannot be launched; shape mismatches are reported first
+    assert _status(tc, lambda: tc.tc_kv_export(p, pool, 0, [4096], [4096], 4096)) == tc.TC_ERR_ARG
+    assert _status(tc, lambda: tc.tc_kv_import(p, pool, 0, [4096], [4096], 4096)) == tc.TC_ERR_ARG
+    pool2 = tc.make_pool(8, 2, 128, 33)
+    assert _status(tc, lambda: tc.tc_kv_export(p, pool2, 0, [4096], [4096], 4096)) == tc.TC_ERR_SHAPE
+
+
 def test_empty_batch_is_a_valid_plan(tc):
     pool = tc.make_pool(8, 2, 128, 4)
     p = tc.Plan(pool, np.zeros(1, np.int32), np.zeros(0, np.int32), np.zeros((0, 1), np.int32), host_only=True)
