@@ -37,6 +37,79 @@ def measured_traffic(workload):
         pass
     return None
 WORKLOADS = ["tiny", "prefill_heavy", "decode_heavy", "pure_decode", "long_prompt"]
+MIGRATE = "kv_migrate"  # not a mixed-batch step: export + import of whole requests, all layers
+
+
+def bench_migrate(args):
+    """Move `n_req` decode requests (lengths of the pure-decode configuration, its head shape) of a
+    32-layer model: tc_kv_export into a transfer buffer, tc_kv_import into other blocks of a second
+    set of pools.  Bytes counted: every page read once and written once, per direction."""
+    import torch
+    import workloads as W
+    import paper_2508_01989_amd as tc
+    sp = W.config_spec(3)
+    n_req, L = 16, 32
+    kv_len = (np.asarray(sp.ctx_len[:n_req]) + 1).astype(np.int64)
+    pages = (kv_len + 15) // 16
+    P = int(pages.sum())
+    nb = P + 64
+    rng = np.random.default_rng(sp.seed)
+
+    def table(seed):
+        ids = np.random.default_rng(seed).permutation(nb).astype(np.int32)
+        t = np.full((n_req, int(pages.max())), W.TABLE_SENTINEL, np.int32)
+        o = 0
+        for s in range(n_req):
+            t[s, :pages[s]] = ids[o:o + pages[s]]
+            o += pages[s]
+        return t
+
+    torch.cuda.set_device(0)
+    n = nb * sp.num_kv_heads * 16 * sp.head_dim
+    src_k = [torch.randint(-30000, 30000, (n,), dtype=torch.int16, device="cuda:0") for _ in range(L)]
+    src_v = [torch.randint(-30000, 30000, (n,), dtype=torch.int16, device="cuda:0") for _ in range(L)]
+    dst_k = [torch.zeros(n, dtype=torch.int16, device="cuda:0") for _ in range(L)]
+    dst_v = [torch.zeros(n, dtype=torch.int16, device="cuda:0") for _ in range(L)]
+    pool = tc.make_pool(sp.num_q_heads, sp.num_kv_heads, sp.head_dim, nb)
+    q_start = np.arange(n_req + 1, dtype=np.int32)
+    ctx = (kv_len - 1).astype(np.int32)
+    stream = torch.cuda.Stream()
+    with torch.cuda.stream(stream):
+        plan_a, plan_b = tc.Plan(pool, q_start, ctx, table(1), stream=stream), tc.Plan(pool, q_start, ctx, table(2), stream=stream)
+        nbytes = tc.tc_kv_transfer_bytes(plan_a, -1, L)
+        buf = torch.empty(nbytes // 2, dtype=torch.int16, device="cuda:0")
+        for _ in range(args.warmup):
+            tc.tc_kv_export(plan_a, pool, -1, src_k, src_v, buf, stream=stream)
+            tc.tc_kv_import(plan_b, pool, -1, dst_k, dst_v, buf, stream=stream)
+        ev = [[torch.cuda.Event(enable_timing=True) for _ in range(3)] for _ in range(args.steps)]
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for i in range(args.steps):
+            ev[i][0].record(stream)
+            tc.tc_kv_export(plan_a, pool, -1, src_k, src_v, buf, stream=stream)
+            ev[i][1].record(stream)
+            tc.tc_kv_import(plan_b, pool, -1, dst_k, dst_v, buf, stream=stream)
+            ev[i][2].record(stream)
+        torch.cuda.synchronize()
+        wall = time.perf_counter() - t0
+    exp_ms = float(np.mean([e[0].elapsed_time(e[1]) for e in ev]))
+    imp_ms = float(np.mean([e[1].elapsed_time(e[2]) for e in ev]))
+    moved = 2 * nbytes  # read + write, per direction
+    ms = wall / args.steps * 1e3
+    gbs = 2 * moved / (ms * 1e-3) / 1e9
+    line = {"metric": "kv_migration_bandwidth", "value": gbs, "unit": "GB/s", "n_gpus": 1, "steps": args.steps,
+            "warmup": args.warmup, "ms_per_step": ms, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+            "dtype": "bf16", "data": "synthetic",
+            "config": {"workload": MIGRATE, "requests": n_req, "layers": L, "num_kv_heads": sp.num_kv_heads,
+                       "head_dim": sp.head_dim, "block_size": 16, "tokens": int(kv_len.sum()), "pages": P,
+                       "transfer_bytes": nbytes},
+            "export_ms": exp_ms, "import_ms": imp_ms,
+            "roofline": {"bound": "hbm", "achieved": 2 * moved / ((exp_ms + imp_ms) * 1e-3) / 1e9, "peak": PEAK_HBM_GBS,
+                         "unit": "GB/s", "frac": 2 * moved / ((exp_ms + imp_ms) * 1e-3) / 1e9 / PEAK_HBM_GBS, "traffic": None,
+                         "kernel": "kv_migrate_kernel (export and import launches averaged)",
+                         "export_GBs": moved / (exp_ms * 1e-3) / 1e9, "import_GBs": moved / (imp_ms * 1e-3) / 1e9,
+                         "algorithmic_bytes": moved}}
+    print(json.dumps(line))
 
 
 def cpu_baseline(batch, work, target_s=15.0):
@@ -86,7 +159,7 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=200)
     ap.add_argument("--warmup", type=int, default=20)
-    ap.add_argument("--workload", default="prefill_heavy", choices=WORKLOADS)
+    ap.add_argument("--workload", default="prefill_heavy", choices=WORKLOADS + [MIGRATE])
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="run a plain 1 GiB device copy three times and exit (counter calibration under rocprofv3 --pmc)")
@@ -110,6 +183,9 @@ def main():
             dst.copy_(src)
         torch.cuda.synchronize()
         print(json.dumps({"calibrate_copy_bytes_each_way": n * 4, "copies": 3}))
+        return
+    if args.workload == MIGRATE:
+        bench_migrate(args)
         return
     idx = WORKLOADS.index(args.workload)
     spec = W.config_spec(idx)

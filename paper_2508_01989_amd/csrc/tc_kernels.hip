@@ -136,7 +136,7 @@ __global__ void __launch_bounds__(256) kv_gather_kernel(const uint16_t *__restri
 // The transfer buffer is [layers][pages][K block | V block] with both blocks in the pool's own
 // layout, so a page moves as 16-byte pieces that are contiguous on both sides; the block id is
 // the only indirection.  Workgroup (x, y) moves page x of the selection for layer y.  A full page
-// is a straight copy with eight loads in flight per thread.  The last page of a sequence may hold
+// is a straight copy with eight non-temporal loads in flight per thread (the data is touched once).  The last page of a sequence may hold
 // fewer than 16 tokens: the export writes zero for the missing ones, the import stores only the
 // real ones (K: 16-byte pieces of real tokens; V, which is token-minor: 2-byte elements).
 struct MigratePools {
