@@ -656,7 +656,7 @@ __global__ void __launch_bounds__(kWgThreads, kWgPerCu)
 // One workgroup per (sequence, KV head); one wavefront per query head; a lane owns D/64 adjacent
 // head-dim elements, so each partial row is one coalesced read.  Lane i first fetches (m_i, l_i) of
 // split i (at most 64 splits per wave pass), the wave reduces the maximum, and the weighted sum runs
-// over the splits with the weights broadcast from those registers.
+// over the splits, in index order, with the weights broadcast from those registers.
 template <int D>
 __global__ void __launch_bounds__(256) split_merge_kernel(const int32_t *__restrict__ items, const float *__restrict__ ws_o,
                                                           const float *__restrict__ ws_ml, uint16_t *__restrict__ out,
@@ -672,6 +672,26 @@ __global__ void __launch_bounds__(256) split_merge_kernel(const int32_t *__restr
         float m_star = -1e30f, den = 0.f;
         for (int base = 0; base < ns; base += 64) {  // 64 splits per pass; passes chained by an online rescale
             const int n = min(64, ns - base);
+            const float *src = ws_o + ((int64_t)(slot0 + base) * G + j) * D + lane * E;
+            // Partial rows are fetched kChunk at a time, all loads of a chunk in flight together; the
+            // first chunk is requested before the weights are known.
+            constexpr int kChunk = 8;
+            float row[kChunk][E];
+            auto fetch = [&](int c0) {
+#pragma unroll
+                for (int u = 0; u < kChunk; u++)
+                    if (c0 + u < n) {
+                        const float *r = src + (int64_t)(c0 + u) * G * D;
+                        if (E == 2) {
+                            const float2 v = *reinterpret_cast<const float2 *>(r);
+                            row[u][0] = v.x;
+                            row[u][E - 1] = v.y;
+                        } else {
+                            row[u][0] = r[0];
+                        }
+                    }
+            };
+            fetch(0);
             const int64_t my_row = (int64_t)(slot0 + base + min(lane, n - 1)) * G + j;
             const float m_i = lane < n ? ws_ml[my_row * 2] : -1e30f;
             const float l_i = lane < n ? ws_ml[my_row * 2 + 1] : 0.f;
@@ -688,16 +708,15 @@ __global__ void __launch_bounds__(256) split_merge_kernel(const int32_t *__restr
             den = den * rescale + wl;
 #pragma unroll
             for (int e = 0; e < E; e++) acc[e] *= rescale;
-            const float *src = ws_o + ((int64_t)(slot0 + base) * G + j) * D + lane * E;
-            for (int i = 0; i < n; i++) {
-                const float w = __shfl(w_i, i, 64);
-                if (E == 2) {
-                    const float2 v = *reinterpret_cast<const float2 *>(src + (int64_t)i * G * D);
-                    acc[0] += w * v.x;
-                    acc[E - 1] += w * v.y;
-                } else {
-                    acc[0] += w * src[(int64_t)i * G * D];
-                }
+            for (int c0 = 0; c0 < n; c0 += kChunk) {
+#pragma unroll
+                for (int u = 0; u < kChunk; u++)
+                    if (c0 + u < n) {
+                        const float w = __shfl(w_i, c0 + u, 64);
+#pragma unroll
+                        for (int e = 0; e < E; e++) acc[e] += w * row[u][e];
+                    }
+                if (c0 + kChunk < n) fetch(c0 + kChunk);
             }
         }
         const float inv = 1.f / den;
