@@ -36,7 +36,7 @@ class tc_plan_info(C.Structure):
     _fields_ = [(n, C.c_int32) for n in
                 ("num_seqs", "total_q", "num_prefill_seqs", "num_decode_seqs", "num_prefill_items",
                  "num_decode_items", "num_merge_items", "num_partials", "split_tokens", "rows_per_prefill_item",
-                 "grid_blocks", "block_threads")] + [("total_pages", C.c_int64)]
+                 "grid_blocks", "block_threads")] + [("total_pages", C.c_int64), ("num_prefill_pieces", C.c_int32)]
 
 
 class TcError(RuntimeError):
@@ -142,7 +142,8 @@ class Plan:
         return int(lib().tc_plan_workspace_bytes(self.handle))
 
     def items(self, kind: int) -> np.ndarray:
-        n = (self.info.num_prefill_items, self.info.num_decode_items, self.info.num_merge_items)[kind]
+        n = (self.info.num_prefill_items, self.info.num_decode_items, self.info.num_merge_items,
+             self.info.num_prefill_pieces)[kind]
         out = np.zeros((n, 8), np.int32)
         _check(lib().tc_plan_copy_items(self.handle, kind, out.ctypes.data_as(C.POINTER(C.c_int32)), n))
         return out

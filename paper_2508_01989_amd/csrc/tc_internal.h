@@ -18,6 +18,8 @@ constexpr int kPrefillRows = 32 * kWgWaves;  // (position, head) rows per prefil
 constexpr int kItemInts = 8;        // int32 fields per work item
 constexpr int kAppendInts = 4;      // int32 fields per append segment: first packed row, tokens, first token index, pool block
 constexpr int kMaxSplitPages = 64;  // a decode split's page ids fit one wavefront register
+constexpr int kPrefillTileTokens = 64;  // KV tokens per LDS tile of the prefill branch
+constexpr int kNumCu = 256;         // compute units the work list is balanced for
 constexpr int kMigrateLayers = 64;  // layers one migration launch covers (their pool pointers travel as kernel arguments)
 constexpr int kMaxLayers = 4096;
 
@@ -25,6 +27,10 @@ constexpr int kMaxLayers = 4096;
 enum { PF_SEQ, PF_KVH, PF_POS0, PF_NPOS, PF_QROW0, PF_CTX, PF_PAGEOFF, PF_NPAGES };
 enum { DC_SEQ, DC_KVH, DC_BEGIN, DC_END, DC_QROW, DC_SLOT, DC_PAGEOFF, DC_PAD };
 enum { MG_SEQ, MG_KVH, MG_QROW, MG_SLOT0, MG_NSPLIT };
+// A prefill piece is what one workgroup runs: KV tiles [T0, T1) of a prefill item.  SLOT is -1 when
+// the piece is the whole item (it writes the output rows); otherwise position i of the item writes
+// its partial result to workspace slot SLOT + i * K (K pieces per item, adjacent slots per position).
+enum { PP_ITEM, PP_T0, PP_T1, PP_SLOT, PP_K };
 
 void set_error(const std::string &msg);
 
@@ -36,17 +42,18 @@ struct tc_plan {
     int S = 0, T = 0;
     int n_prefill_seqs = 0, n_decode_seqs = 0;
     int n_prefill = 0, n_decode = 0, n_merge = 0, n_partials = 0;
+    int n_pieces = 0;  // prefill workgroups: one per piece (an item whose KV range is not cut is one piece)
     int split_tokens = 0;
     int64_t total_pages = 0;
     std::vector<int32_t> q_start, ctx_len, page_off;  // host copies
     // One int32 buffer uploaded as a whole; offsets (in int32 units) of its sections.
     std::vector<int32_t> host;
-    size_t off_append = 0, off_pages = 0, off_valid = 0, off_prefill = 0, off_decode = 0, off_merge = 0;  // off_valid: tokens (1..16) each page holds
+    size_t off_append = 0, off_pages = 0, off_valid = 0, off_prefill = 0, off_pieces = 0, off_decode = 0, off_merge = 0;  // off_valid: tokens (1..16) each page holds
     int n_append = 0;  // (sequence, page) segments written by the append
     int32_t *dev = nullptr;  // device copy of `host`, nullptr for host-only plans
     int device = -1;
 
-    int grid_blocks() const { return n_prefill + (n_decode + tc::kWgWaves - 1) / tc::kWgWaves; }
+    int grid_blocks() const { return n_pieces + (n_decode + tc::kWgWaves - 1) / tc::kWgWaves; }
     size_t workspace_bytes() const {
         // per partial: G heads x (D accumulators + running max + running sum), fp32
         return (size_t)n_partials * (size_t)G * (size_t)(D + 2) * sizeof(float);

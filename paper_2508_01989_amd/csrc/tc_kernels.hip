@@ -40,6 +40,7 @@ struct AttnArgs {
     uint16_t *out;
     const int32_t *pages;    // page ids of all sequences, CSR by sequence
     const int32_t *prefill;  // work items
+    const int32_t *pieces;   // one per prefill workgroup: item and KV tile range
     const int32_t *decode;
     float *ws_o;             // [n_partials][G][D]
     float *ws_ml;            // [n_partials][G][2]  (running max in the log2 domain, running sum)
@@ -260,6 +261,7 @@ __device__ __forceinline__ void prefill_fetch(const AttnArgs &A, int kvh, int pa
                                               int lane) {
     using C = PrefillCfg<D>;
     static_assert(C::kTilePages == kWgWaves, "one wave per page of a tile");
+    static_assert(C::kTileTokens == kPrefillTileTokens, "the planner cuts KV ranges in units of this tile");
     typedef const __attribute__((address_space(1))) void *gptr_t;
     typedef __attribute__((address_space(3))) void *lptr_t;
     const int64_t base = ((int64_t)__builtin_amdgcn_readfirstlane(page_id) * A.Hkv + kvh) * (int64_t)(kBlock * D);
@@ -311,7 +313,7 @@ __device__ __forceinline__ float half_swap_sum(float v) {
 }
 
 template <int D>
-__device__ void prefill_item(const AttnArgs &A, const int32_t *__restrict__ it, char *lds) {
+__device__ void prefill_item(const AttnArgs &A, const int32_t *__restrict__ it, const int32_t *__restrict__ pc, char *lds) {
     using C = PrefillCfg<D>;
     constexpr int KS = D / 16;  // k-steps of the QK^T product
     constexpr int MT = D / 32;  // 32-row tiles of O^T
@@ -333,7 +335,8 @@ __device__ void prefill_item(const AttnArgs &A, const int32_t *__restrict__ it, 
     const int r_lo = min(wave * 32, n_rows - 1), r_hi = min(wave * 32 + 31, n_rows - 1);
     const int wave_pmin = ctx + pos0 + r_lo / G, wave_pmax = ctx + pos0 + r_hi / G;
     const int kv_len = ctx + pos0 + npos;  // tokens this workgroup may read (all appended already)
-    const int n_tiles = (kv_len - 1) / C::kTileTokens + 1;
+    // KV tiles [t_begin, t_end) of the item; p_slot < 0: the whole range, results go to `out`
+    const int t_begin = pc[PP_T0], t_end = pc[PP_T1], p_slot = pc[PP_SLOT], p_k = pc[PP_K];
     const float c_log2 = A.scale_log2;
     const int v_lane_off = n * 32 + ((hh ^ ((n >> 3) & 1)) * 16);  // this lane's 16 bytes inside a 32-row V^T tile
 
@@ -357,18 +360,18 @@ __device__ void prefill_item(const AttnArgs &A, const int32_t *__restrict__ it, 
 #pragma unroll
     for (int e = 0; e < 8; e++) ones[e] = (__bf16)1.0f;
 
-    int page_id = prefill_page_id<D>(pages, n_pages, 0, wave);
+    int page_id = prefill_page_id<D>(pages, n_pages, t_begin, wave);
     prefill_fetch<D>(A, kvh, page_id, lds, lds + 2 * C::kTileBytes, wave, lane);
-    page_id = prefill_page_id<D>(pages, n_pages, 1, wave);
+    page_id = prefill_page_id<D>(pages, n_pages, t_begin + 1, wave);
     wait_all_loads();
-    if (kv_len < C::kTileTokens) prefill_fix_tail<D>(lds + 2 * C::kTileBytes, 0, wave, lane, kv_len);
+    if ((t_begin + 1) * C::kTileTokens > kv_len) prefill_fix_tail<D>(lds + 2 * C::kTileBytes, t_begin, wave, lane, kv_len);
     __syncthreads();
 
-    for (int tile = 0; tile < n_tiles; tile++) {
-        const int cur = tile & 1;
+    for (int tile = t_begin; tile < t_end; tile++) {
+        const int cur = (tile - t_begin) & 1;
         const char *ks = lds + cur * C::kTileBytes;
         const char *vs = lds + 2 * C::kTileBytes + cur * C::kTileBytes;
-        const bool more = tile + 1 < n_tiles;
+        const bool more = tile + 1 < t_end;
         if (more) {  // stage cur^1 was last read before the barrier that ended the previous iteration
             prefill_fetch<D>(A, kvh, page_id, lds + (cur ^ 1) * C::kTileBytes, lds + 2 * C::kTileBytes + (cur ^ 1) * C::kTileBytes, wave, lane);
             page_id = prefill_page_id<D>(pages, n_pages, tile + 2, wave);
@@ -448,6 +451,26 @@ __device__ void prefill_item(const AttnArgs &A, const int32_t *__restrict__ it, 
     }
 
     l_run = kRowSumOnMfma ? lsum[0] : half_swap_sum(l_run);
+    if (p_slot >= 0) {
+        // A piece of a cut item: unnormalised accumulators, running maximum (log2 domain) and row sum
+        // go to the workspace, in the partial layout the decode splits use; rows that see no key of
+        // this piece carry (m, l, o) = (-1e30, 0, 0) and get weight 0 in the merge.
+        if (row_valid) {
+            const int64_t prow = ((int64_t)(p_slot + (Rc / G) * p_k)) * G + Rc % G;
+            float *dst = A.ws_o + prow * D + 4 * hh;
+#pragma unroll
+            for (int c = 0; c < MT; c++)
+#pragma unroll
+                for (int q4 = 0; q4 < 4; q4++)
+                    *reinterpret_cast<f32x4 *>(dst + 32 * c + 8 * q4) =
+                        f32x4{o[c][4 * q4], o[c][4 * q4 + 1], o[c][4 * q4 + 2], o[c][4 * q4 + 3]};
+            if (hh == 0) {
+                A.ws_ml[prow * 2] = m_run;
+                A.ws_ml[prow * 2 + 1] = l_run;
+            }
+        }
+        return;
+    }
     const float inv = 1.f / l_run;
     if (row_valid) {
 #pragma unroll
@@ -634,16 +657,18 @@ template <int D>
 __global__ void __launch_bounds__(kWgThreads, kWgPerCu)
     mixed_attention_kernel(const uint16_t *__restrict__ k_pool, const uint16_t *__restrict__ v_pool,
                            const uint16_t *__restrict__ q, uint16_t *__restrict__ out, const int32_t *__restrict__ pages,
-                           const int32_t *__restrict__ prefill, const int32_t *__restrict__ decode,
-                           float *__restrict__ ws_o, float *__restrict__ ws_ml, const AttnScalars sc) {
+                           const int32_t *__restrict__ prefill, const int32_t *__restrict__ pieces,
+                           const int32_t *__restrict__ decode, float *__restrict__ ws_o, float *__restrict__ ws_ml,
+                           const AttnScalars sc) {
     extern __shared__ __align__(16) char lds[];
     AttnArgs A;
-    A.k_pool = k_pool; A.v_pool = v_pool; A.q = q; A.out = out; A.pages = pages; A.prefill = prefill; A.decode = decode;
+    A.k_pool = k_pool; A.v_pool = v_pool; A.q = q; A.out = out; A.pages = pages; A.prefill = prefill; A.pieces = pieces; A.decode = decode;
     A.ws_o = ws_o; A.ws_ml = ws_ml;
     A.n_prefill = sc.n_prefill; A.n_decode = sc.n_decode; A.Hq = sc.Hq; A.Hkv = sc.Hkv; A.G = sc.G;
     A.scale_log2 = sc.scale_log2;
     if ((int)blockIdx.x < A.n_prefill) {
-        prefill_item<D>(A, prefill + (int64_t)blockIdx.x * kItemInts, lds);
+        const int32_t *pc = pieces + (int64_t)blockIdx.x * kItemInts;
+        prefill_item<D>(A, prefill + (int64_t)pc[PP_ITEM] * kItemInts, pc, lds);
     } else {
         const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
         const int idx = ((int)blockIdx.x - A.n_prefill) * kWgWaves + wave;
@@ -820,8 +845,8 @@ static int launch_attention_d(const tc_plan *p, const AttnArgs &A, hipStream_t s
     const int grid = p->grid_blocks();
     const AttnScalars sc = {A.n_prefill, A.n_decode, A.Hq, A.Hkv, A.G, A.scale_log2};
     if (grid > 0)
-        mixed_attention_kernel<D><<<grid, kWgThreads, p->n_prefill > 0 ? lds : 0, st>>>(A.k_pool, A.v_pool, A.q, A.out, A.pages, A.prefill,
-                                                                                 A.decode, A.ws_o, A.ws_ml, sc);
+        mixed_attention_kernel<D><<<grid, kWgThreads, p->n_pieces > 0 ? lds : 0, st>>>(A.k_pool, A.v_pool, A.q, A.out, A.pages, A.prefill,
+                                                                                A.pieces, A.decode, A.ws_o, A.ws_ml, sc);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return (int)e;
     if (p->n_merge > 0)
@@ -838,10 +863,11 @@ int launch_attention(const tc_plan *p, const tc_kv_pool *pool, const void *q, vo
     A.out = (uint16_t *)out;
     A.pages = p->dev + p->off_pages;
     A.prefill = p->dev + p->off_prefill;
+    A.pieces = p->dev + p->off_pieces;
     A.decode = p->dev + p->off_decode;
     A.ws_o = (float *)workspace;
     A.ws_ml = A.ws_o ? A.ws_o + (size_t)p->n_partials * p->G * p->D : nullptr;
-    A.n_prefill = p->n_prefill;
+    A.n_prefill = p->n_pieces;  // workgroups of the prefill branch
     A.n_decode = p->n_decode;
     A.Hq = p->Hq;
     A.Hkv = p->Hkv;

@@ -2,6 +2,7 @@
 // piggybacked decodes, paper Sec. 2.2 / 3.2) into the integer work list the fused
 // attention kernel consumes.  Runs once per iteration; every layer reuses the plan.
 #include <algorithm>
+#include <cmath>
 #include <cstring>
 #include <new>
 
@@ -34,6 +35,28 @@ static int choose_split(int64_t decode_token_heads) {
     for (int split = kMaxSplitPages * kBlock; split > 128; split /= 2)
         if (decode_token_heads / split >= want_items) return split;
     return 128;
+}
+
+// When a batch has few prefill row blocks (a small chunk, as on a decode-heavy instance), each of
+// them sweeps its whole KV range in one workgroup while most of the chip idles, and that sweep is the
+// iteration's critical path.  Then the KV range of a row block is cut into k pieces that run as
+// separate workgroups and are combined by the merge launch.  k is the smallest count that brings the
+// sweep down to the time the decode branch needs anyway (both estimated from measured rates: about
+// 2 us per 64-token tile, about 5 TB/s for the decode reads), at most 8, at least 8 tiles per piece,
+// and never more pieces than workgroup slots; batches whose row blocks already fill a quarter of the
+// slots are left alone (k = 1).
+template <class Tile>
+static void choose_prefill_cuts(Tile *tiles, size_t n, int Hkv, int64_t decode_bytes) {
+    const int64_t slots = (int64_t)kWgPerCu * kNumCu;
+    const int64_t items = (int64_t)n * Hkv;
+    if (items == 0 || items * 4 > slots) return;  // with more row blocks than that, cutting measured slower
+    const int k_cap = (int)std::min<int64_t>(8, slots / items);
+    const double t_decode_us = std::max(16.0, (double)decode_bytes / 5.0e6);
+    for (size_t i = 0; i < n; i++) {
+        const int n_tiles = (int)((tiles[i].cost - 1) / kPrefillTileTokens) + 1;
+        const int want = (int)std::ceil(n_tiles * 2.0 / t_decode_us);
+        tiles[i].k = std::max(1, std::min({want, k_cap, n_tiles / 8}));
+    }
 }
 
 tc_status build_plan(const tc_kv_pool *pool, const tc_batch *b, tc_plan **out) {
@@ -82,21 +105,40 @@ tc_status build_plan(const tc_kv_pool *pool, const tc_batch *b, tc_plan **out) {
     p->total_pages = pages;
     p->split_tokens = choose_split(decode_tokens * Hkv);
 
-    // ---- section sizes
+    // ---- prefill items (row blocks) and how many pieces each item's KV range is cut into
     const int pos_per_item = kPrefillRows / G;
-    int64_t n_prefill = 0, n_decode = 0, n_merge = 0, n_partials = 0;
+    struct Tile { int seq, pos0, npos; int64_t cost; int k; };
+    std::vector<Tile> tiles;
     for (int s = 0; s < S; s++) {
         const int q = p->q_start[s + 1] - p->q_start[s];
-        if (q > 1) n_prefill += (int64_t)((q + pos_per_item - 1) / pos_per_item) * Hkv;
-        else {
+        if (q <= 1) continue;
+        for (int pos0 = 0; pos0 < q; pos0 += pos_per_item) {
+            const int npos = std::min(pos_per_item, q - pos0);
+            tiles.push_back({s, pos0, npos, (int64_t)p->ctx_len[s] + pos0 + npos, 1});
+        }
+    }
+    // heaviest (latest positions, longest KV range) first
+    std::stable_sort(tiles.begin(), tiles.end(), [](const Tile &x, const Tile &y) { return x.cost > y.cost; });
+    choose_prefill_cuts(tiles.data(), tiles.size(), Hkv, decode_tokens * Hkv * D * 4);
+
+    // ---- section sizes
+    int64_t n_prefill = (int64_t)tiles.size() * Hkv, n_pieces = 0, n_decode = 0, n_merge = 0, n_partials = 0;
+    for (const Tile &t : tiles) {
+        n_pieces += (int64_t)t.k * Hkv;
+        if (t.k > 1) { n_merge += (int64_t)t.npos * Hkv; n_partials += (int64_t)t.k * t.npos * Hkv; }
+    }
+    for (int s = 0; s < S; s++) {
+        const int q = p->q_start[s + 1] - p->q_start[s];
+        if (q == 1) {
             const int64_t kv = (int64_t)p->ctx_len[s] + 1;
             const int64_t ns = (kv + p->split_tokens - 1) / p->split_tokens;
             n_decode += ns * Hkv;
             if (ns > 1) { n_merge += Hkv; n_partials += ns * Hkv; }
         }
     }
-    if (n_prefill + n_decode >= ((int64_t)1 << 28)) { delete p; return fail(TC_ERR_SPAN, "batch too large"); }
-    p->n_prefill = (int)n_prefill; p->n_decode = (int)n_decode; p->n_merge = (int)n_merge; p->n_partials = (int)n_partials;
+    if (n_pieces + n_decode >= ((int64_t)1 << 28) || n_partials >= ((int64_t)1 << 28)) { delete p; return fail(TC_ERR_SPAN, "batch too large"); }
+    p->n_prefill = (int)n_prefill; p->n_pieces = (int)n_pieces; p->n_decode = (int)n_decode; p->n_merge = (int)n_merge;
+    p->n_partials = (int)n_partials;
 
     // append segments: the rows a sequence adds to one page (1..16 consecutive token indices)
     int64_t n_append = 0;
@@ -109,7 +151,8 @@ tc_status build_plan(const tc_kv_pool *pool, const tc_batch *b, tc_plan **out) {
     p->off_pages = p->off_append + (size_t)n_append * kAppendInts;
     p->off_valid = p->off_pages + (size_t)pages;
     p->off_prefill = p->off_valid + (size_t)pages;
-    p->off_decode = p->off_prefill + (size_t)n_prefill * kItemInts;
+    p->off_pieces = p->off_prefill + (size_t)n_prefill * kItemInts;
+    p->off_decode = p->off_pieces + (size_t)n_pieces * kItemInts;
     p->off_merge = p->off_decode + (size_t)n_decode * kItemInts;
     const size_t total = p->off_merge + (size_t)n_merge * kItemInts;
     p->host.assign(std::max<size_t>(total, 1), 0);
@@ -146,33 +189,44 @@ tc_status build_plan(const tc_kv_pool *pool, const tc_batch *b, tc_plan **out) {
         }
     }
 
-    // ---- prefill items: heaviest (latest positions, longest KV range) first; KV head is the
-    // fastest index so that workgroup id % Hkv names the KV head (one L2 per 8th workgroup).
-    struct Tile { int seq, pos0, npos; int64_t cost; };
-    std::vector<Tile> tiles;
-    for (int s = 0; s < S; s++) {
-        const int q = p->q_start[s + 1] - p->q_start[s];
-        if (q <= 1) continue;
-        for (int pos0 = 0; pos0 < q; pos0 += pos_per_item) {
-            const int npos = std::min(pos_per_item, q - pos0);
-            tiles.push_back({s, pos0, npos, (int64_t)p->ctx_len[s] + pos0 + npos});
+    // ---- prefill items in `tiles` order; KV head is the fastest index so that workgroup id % Hkv
+    // names the KV head (one L2 per 8th workgroup).  Then the pieces, most tiles first.
+    int32_t next_slot = 0;
+    int32_t *mg = H + p->off_merge;
+    {
+        int32_t *pf = H + p->off_prefill;
+        struct Piece { int item, t0, t1, slot, k; };
+        std::vector<Piece> pieces;
+        pieces.reserve((size_t)n_pieces);
+        int item = 0;
+        for (const Tile &t : tiles) {
+            const int n_tiles = (int)((t.cost - 1) / kPrefillTileTokens) + 1;
+            for (int h = 0; h < Hkv; h++, pf += kItemInts, item++) {
+                pf[PF_SEQ] = t.seq; pf[PF_KVH] = h; pf[PF_POS0] = t.pos0; pf[PF_NPOS] = t.npos;
+                pf[PF_QROW0] = p->q_start[t.seq]; pf[PF_CTX] = p->ctx_len[t.seq];
+                pf[PF_PAGEOFF] = p->page_off[t.seq]; pf[PF_NPAGES] = p->page_off[t.seq + 1] - p->page_off[t.seq];
+                if (t.k == 1) { pieces.push_back({item, 0, n_tiles, -1, 1}); continue; }
+                for (int c = 0; c < t.k; c++)
+                    pieces.push_back({item, (int)((int64_t)n_tiles * c / t.k), (int)((int64_t)n_tiles * (c + 1) / t.k), next_slot + c, t.k});
+                for (int i = 0; i < t.npos; i++, mg += kItemInts) {
+                    mg[MG_SEQ] = t.seq; mg[MG_KVH] = h; mg[MG_QROW] = p->q_start[t.seq] + t.pos0 + i;
+                    mg[MG_SLOT0] = next_slot + i * t.k; mg[MG_NSPLIT] = t.k;
+                }
+                next_slot += t.k * t.npos;
+            }
+        }
+        std::stable_sort(pieces.begin(), pieces.end(), [](const Piece &x, const Piece &y) { return x.t1 - x.t0 > y.t1 - y.t0; });
+        int32_t *pc = H + p->off_pieces;
+        for (const Piece &x : pieces) {
+            pc[PP_ITEM] = x.item; pc[PP_T0] = x.t0; pc[PP_T1] = x.t1; pc[PP_SLOT] = x.slot; pc[PP_K] = x.k;
+            pc += kItemInts;
         }
     }
-    std::stable_sort(tiles.begin(), tiles.end(), [](const Tile &x, const Tile &y) { return x.cost > y.cost; });
-    int32_t *pf = H + p->off_prefill;
-    for (const Tile &t : tiles)
-        for (int h = 0; h < Hkv; h++, pf += kItemInts) {
-            pf[PF_SEQ] = t.seq; pf[PF_KVH] = h; pf[PF_POS0] = t.pos0; pf[PF_NPOS] = t.npos;
-            pf[PF_QROW0] = p->q_start[t.seq]; pf[PF_CTX] = p->ctx_len[t.seq];
-            pf[PF_PAGEOFF] = p->page_off[t.seq]; pf[PF_NPAGES] = p->page_off[t.seq + 1] - p->page_off[t.seq];
-        }
 
     // ---- decode items: longest splits first so the tail of the launch is short work.
     struct Split { int seq, begin, end, idx, nsplit; };
     std::vector<Split> splits;
     std::vector<int32_t> slot0(S, -1);
-    int32_t next_slot = 0;
-    int32_t *mg = H + p->off_merge;
     for (int s = 0; s < S; s++) {
         if (p->q_start[s + 1] - p->q_start[s] != 1) continue;
         const int kv = p->ctx_len[s] + 1;
@@ -233,6 +287,7 @@ tc_status tc_plan_get_info(const tc_plan *p, tc_plan_info *info) {
     info->split_tokens = p->split_tokens; info->rows_per_prefill_item = tc::kPrefillRows;
     info->grid_blocks = p->grid_blocks(); info->block_threads = tc::kWgThreads;
     info->total_pages = p->total_pages;
+    info->num_prefill_pieces = p->n_pieces;
     return TC_OK;
 }
 
@@ -242,7 +297,8 @@ tc_status tc_plan_copy_items(const tc_plan *p, int32_t kind, int32_t *dst, size_
     if (kind == 0) { off = p->off_prefill; n = p->n_prefill; }
     else if (kind == 1) { off = p->off_decode; n = p->n_decode; }
     else if (kind == 2) { off = p->off_merge; n = p->n_merge; }
-    else { tc::set_error("kind must be 0, 1 or 2"); return TC_ERR_ARG; }
+    else if (kind == 3) { off = p->off_pieces; n = p->n_pieces; }
+    else { tc::set_error("kind must be 0, 1, 2 or 3"); return TC_ERR_ARG; }
     n = std::min(n, cap_items);
     std::memcpy(dst, p->host.data() + off, n * tc::kItemInts * sizeof(int32_t));
     return TC_OK;

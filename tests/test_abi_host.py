@@ -123,16 +123,13 @@ def test_empty_batch_is_a_valid_plan(tc):
     assert p.info.grid_blocks == 0 and p.workspace_bytes == 0
 
 
-@pytest.mark.parametrize("idx", [0, 1, 2, 3, 4])
-def test_work_list_covers_the_batch_exactly(tc, idx):
-    sp = W.config_spec(idx)
-    table, mb, nb = W.make_tables(sp, np.random.default_rng(3))
+def check_work_list(tc, sp, table, nb):
     qs = np.zeros(sp.num_seqs + 1, np.int32)
     qs[1:] = np.cumsum(sp.q_len)
     pool = tc.make_pool(sp.num_q_heads, sp.num_kv_heads, sp.head_dim, nb)
     p = tc.Plan(pool, qs, sp.ctx_len, table, host_only=True)
     info, G, Hkv = p.info, sp.num_q_heads // sp.num_kv_heads, sp.num_kv_heads
-    pf, dc, mg = p.items(0), p.items(1), p.items(2)
+    pf, dc, mg, pc = p.items(0), p.items(1), p.items(2), p.items(3)
     # prefill: every (sequence, KV head) has its positions covered once, in tiles of <= rows_per_prefill_item/G positions
     for s in np.flatnonzero(sp.q_len > 1):
         for h in range(Hkv):
@@ -146,20 +143,69 @@ def test_work_list_covers_the_batch_exactly(tc, idx):
     # heaviest prefill tiles first; KV head is the fastest index
     cost = pf[:, 5] + pf[:, 2] + pf[:, 3]
     assert np.all(np.diff(cost[::Hkv]) <= 0) and np.all(pf[:, 1] == np.arange(len(pf)) % Hkv)
-    # decode: splits tile [0, kv_len) page-aligned, <= 64 pages each, slots unique and dense
+    # pieces: the 64-token KV tiles of every item are covered once, by 1 piece (writes out) or by k pieces
+    # (partial slots), most tiles first
+    assert len(pc) == info.num_prefill_pieces
     slots = []
+    merge_expected = []
+    for i, item in enumerate(pf):
+        mine = pc[pc[:, 0] == i]
+        mine = mine[np.argsort(mine[:, 1])]
+        n_tiles = (int(cost[i]) - 1) // 64 + 1
+        k = len(mine)
+        assert mine[0, 1] == 0 and mine[-1, 2] == n_tiles and np.all(mine[1:, 1] == mine[:-1, 2])
+        assert np.all(mine[:, 2] > mine[:, 1]) and np.all(mine[:, 4] == k)
+        if k == 1:
+            assert mine[0, 3] == -1
+        else:
+            base = int(mine[0, 3])
+            assert mine[:, 3].tolist() == [base + c for c in range(k)]
+            for pos in range(int(item[3])):
+                slots += [base + pos * k + c for c in range(k)]
+                merge_expected.append((int(item[0]), int(item[1]), int(item[4] + item[2] + pos), base + pos * k, k))
+    assert np.all(np.diff(pc[:, 2] - pc[:, 1]) <= 0)
+    # decode: splits tile [0, kv_len) page-aligned, <= 64 pages each
     for s in np.flatnonzero(sp.q_len == 1):
         it = dc[(dc[:, 0] == s) & (dc[:, 1] == 0)]
         it = it[np.argsort(it[:, 2])]
         assert it[0, 2] == 0 and np.all(it[1:, 2] == it[:-1, 3]) and it[-1, 3] == sp.kv_len[s]
         assert np.all(it[:, 2] % 16 == 0) and np.all(it[:, 3] - it[:, 2] <= 1024)
         assert np.all((it[:, 5] >= 0) == (len(it) > 1))
-    used = dc[dc[:, 5] >= 0, 5]
-    assert len(used) == info.num_partials and sorted(used.tolist()) == list(range(info.num_partials))
     assert np.all(np.diff((dc[:, 3] - dc[:, 2])[::Hkv]) <= 0)
-    # merge items name exactly the slots of their splits
-    for m in mg:
-        mine = dc[(dc[:, 0] == m[0]) & (dc[:, 1] == m[1])]
-        assert sorted(mine[:, 5].tolist()) == list(range(m[3], m[3] + m[4]))
+    # partial slots: unique and dense over decode splits and prefill pieces together
+    slots += dc[dc[:, 5] >= 0, 5].tolist()
+    assert len(slots) == info.num_partials and sorted(slots) == list(range(info.num_partials))
+    # merge items name exactly the slots of their splits / pieces
+    for s in np.flatnonzero(sp.q_len == 1):
+        for h in range(Hkv):
+            mine = dc[(dc[:, 0] == s) & (dc[:, 1] == h)]
+            if len(mine) > 1:
+                merge_expected.append((int(s), h, int(qs[s]), int(mine[:, 5].min()), len(mine)))
+                assert sorted(mine[:, 5].tolist()) == list(range(mine[:, 5].min(), mine[:, 5].min() + len(mine)))
+    assert sorted(merge_expected) == sorted(tuple(int(x) for x in m[:5]) for m in mg)
     assert p.workspace_bytes == info.num_partials * G * (sp.head_dim + 2) * 4
-    assert info.grid_blocks == info.num_prefill_items + -(-info.num_decode_items // (info.block_threads // 64))
+    assert info.grid_blocks == info.num_prefill_pieces + -(-info.num_decode_items // (info.block_threads // 64))
+    return info
+
+
+@pytest.mark.parametrize("idx", [0, 1, 2, 3, 4])
+def test_work_list_covers_the_batch_exactly(tc, idx):
+    sp = W.config_spec(idx)
+    table, mb, nb = W.make_tables(sp, np.random.default_rng(3))
+    info = check_work_list(tc, sp, table, nb)
+    assert info.num_prefill_pieces == info.num_prefill_items  # these batches are not cut
+
+
+@pytest.mark.parametrize("name,Hq,Hkv,q_len,ctx,cut", [
+    ("small chunk, few short decodes", 32, 8, [128] + [1] * 16, [2048] + [300] * 16, True),
+    ("small chunk alone", 32, 8, [256], [4000], True),
+    ("ragged chunk, G=5", 10, 2, [77, 1], [1500, 40], True),
+    ("small chunk under a long decode phase", 32, 8, [128] + [1] * 256, [2048] + [3000] * 256, False),
+    ("short context", 32, 8, [128], [100], False),
+])
+def test_small_prefill_batches_are_cut_into_kv_pieces(tc, name, Hq, Hkv, q_len, ctx, cut):
+    sp = W.custom_spec(name, Hq, Hkv, 128, q_len, ctx)
+    table, mb, nb = W.make_tables(sp, np.random.default_rng(5))
+    info = check_work_list(tc, sp, table, nb)
+    assert (info.num_prefill_pieces > info.num_prefill_items) == cut
+    assert info.num_prefill_pieces <= 8 * info.num_prefill_items

@@ -72,6 +72,13 @@ SMALL = {
     "gqa_g5": (10, 2, 128, [120, 1], [0, 260]),
     "head_dim_64": (8, 8, 64, [64, 1, 1, 1, 1], [0, 36, 63, 99, 127]),
     "head_dim_64_gqa": (8, 2, 64, [200, 1, 1], [45, 1000, 17]),
+    # few prefill row blocks over a long context: their KV ranges are cut into pieces that run as
+    # separate workgroups and are merged (4, 3, 2 and 8 pieces)
+    "cut_small_chunk_long_context": (32, 8, 128, [128, 1, 1], [2000, 100, 50]),
+    "cut_ragged_rows": (8, 2, 128, [77], [1500]),
+    "cut_g1_head_dim_64": (4, 4, 64, [100, 1], [900, 30]),
+    "cut_eight_pieces": (32, 8, 128, [64], [5000]),
+    "cut_chunk_at_unaligned_offset": (16, 4, 128, [50, 1], [1111, 700]),
 }
 
 
@@ -79,7 +86,8 @@ SMALL = {
 def test_small_cases_match_oracle(H, name):
     Hq, Hkv, D, q_len, ctx = SMALL[name]
     b = W.make_batch(W.custom_spec(name, Hq, Hkv, D, q_len, ctx, seed=zlib.crc32(name.encode()) % 10007))
-    run_and_compare(H, b, name)
+    _, db = run_and_compare(H, b, name)
+    assert (db.plan.info.num_prefill_pieces > db.plan.info.num_prefill_items) == name.startswith("cut_")
 
 
 def test_config0_tiny_full(H):
