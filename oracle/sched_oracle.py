@@ -80,7 +80,7 @@ def prefill_schedule(instances, req_len, transfer_bytes, link_bytes_per_s, ttft_
 def pick_instance(types, memory_used, capacity, want, need, stay=-1):
     def fits(i):
         return types[i] == want and memory_used[i] + need <= capacity[i]
-    if stay >= 0 and fits(stay):
+    if 0 <= stay < len(types) and fits(stay):  # an index outside the instance list means no preference
         return stay
     ok = [i for i in range(len(types)) if fits(i)]
     if not ok:

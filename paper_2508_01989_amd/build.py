@@ -9,6 +9,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libtc_mi355x.so")
+SCHED_LIB = os.path.join(HERE, "libtc_sched.so")  # host-only scheduling core, built with the host compiler
 SOURCES = ["tc_plan.cpp", "tc_api.cpp", "tc_kernels.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared", "-fno-gpu-rdc",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
@@ -34,5 +35,20 @@ def build(verbose: bool = False, extra=()) -> str:
     return LIB
 
 
+def build_sched(verbose: bool = False) -> str:
+    """The scheduling core has no GPU code: plain g++, so it also loads where no ROCm runtime is."""
+    cmd = [os.environ.get("CXX", "g++"), "-O2", "-std=c++17", "-fPIC", "-shared", "-Wall", "-Wextra", "-ffp-contract=off",
+           "-I", os.path.join(ROOT, "include"), os.path.join(CSRC, "tc_sched.cpp"), "-o", SCHED_LIB]
+    if verbose:
+        print(" ".join(cmd))
+    r = subprocess.run(cmd, capture_output=True, text=True)
+    if r.returncode != 0:
+        raise RuntimeError("g++ failed:\n" + r.stderr)
+    if verbose and r.stderr.strip():
+        print(r.stderr)
+    return SCHED_LIB
+
+
 if __name__ == "__main__":
+    print(build_sched(verbose=True))
     print(build(verbose=True, extra=[a for a in sys.argv[1:] if a.startswith("-")]))
