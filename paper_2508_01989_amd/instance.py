@@ -35,6 +35,7 @@ class Request:
     done: int = 0            # positions whose K/V are cached (= processed)
     blocks: list = field(default_factory=list)
     where: int = -1          # instance currently holding the KV cache
+    ready: float = 0.0       # virtual time from which the current instance may schedule the request
     decode_start_time: float = 0.0
     decode_start_done: int = 0   # value of `done` when decoding (re)started on the current instance
     first_token_time: float = None
@@ -81,6 +82,11 @@ class Instance:
         for _ in range(need):
             req.blocks.append(self.free.pop())
 
+    def reserve(self, req):
+        """Blocks for every position the request will ever hold here, taken when it is first scheduled
+        (or when it migrates in), so that a running request can never run out of memory."""
+        self.ensure_blocks(req, req.n_positions)
+
     def release(self, req):
         self.free.extend(reversed(req.blocks))
         req.blocks = []
@@ -89,22 +95,49 @@ class Instance:
     def has_work(self):
         return bool(self.queue or self.decodes)
 
+    def next_time(self):
+        """Virtual time at which the next iteration of this instance can start."""
+        ready = [r.ready for r in self.queue[:1] + self.decodes]
+        return max(self.clock, min(ready)) if ready else self.clock
+
     def step(self, cm):
         """Form the batch (token budget = chunk size), run every layer, advance the clock.
         Returns the requests whose prefill completed and those that finished in this iteration."""
-        segs, n_pf = sched.form_batch(self.chunk, [(r.prompt_len, r.done) for r in self.queue],
-                                      [r.done for r in self.decodes])
-        reqs = [self.queue[i] for i, _, _ in segs[:n_pf]] + [self.decodes[i] for i, _, _ in segs[n_pf:]]
+        queue, decodes = self._schedulable()
+        if not queue and not decodes:  # everything here becomes ready later: idle until then
+            self.clock = min(r.ready for r in self.queue + self.decodes if r.ready > self.clock)
+            queue, decodes = self._schedulable()
+        segs, n_pf = sched.form_batch(self.chunk, [(r.prompt_len, r.done) for r in queue], [r.done for r in decodes])
+        if not segs:
+            raise RuntimeError(f"instance {self.index}: nothing can be scheduled (chunk {self.chunk}, "
+                               f"{len(self.queue)} queued, {len(self.free)} free blocks)")
+        reqs = [queue[i] for i, _, _ in segs[:n_pf]] + [decodes[i] for i, _, _ in segs[n_pf:]]
         q_len = np.array([s[1] for s in segs], np.int32)
         ctx = np.array([s[2] for s in segs], np.int32)
         for r, n, c in zip(reqs, q_len, ctx):
-            assert c == r.done
-            self.ensure_blocks(r, int(c + n))
+            assert c == r.done and (int(c + n) + BLOCK - 1) // BLOCK <= len(r.blocks)
         q_start = np.concatenate([[0], np.cumsum(q_len)]).astype(np.int32)
         T = int(q_start[-1])
         if not self.dry:
             self._run_layers(reqs, q_len, ctx, q_start)
         return self._account(cm, reqs, q_len, ctx, n_pf, T)
+
+    def _schedulable(self):
+        """Queue entries (FCFS, up to the first that has not arrived or cannot get its blocks yet) and
+        running decodes whose KV cache has arrived."""
+        queue = []
+        for r in self.queue:
+            if r.ready > self.clock:
+                break
+            if not r.blocks:
+                need = (r.n_positions + BLOCK - 1) // BLOCK
+                if need > self.num_blocks:
+                    raise MemoryError(f"request {r.rid} needs {need} blocks, instance {self.index} has {self.num_blocks}")
+                if need > len(self.free):
+                    break
+                self.reserve(r)
+            queue.append(r)
+        return queue, [r for r in self.decodes if r.ready <= self.clock]
 
     def _run_layers(self, reqs, q_len, ctx, q_start):
         width = max(len(r.blocks) for r in reqs)
@@ -174,13 +207,14 @@ class Cluster:
                       queue=[(r.prompt_len, r.done) for r in x.queue]) for x in self.inst]
         transfer = req.prompt_len * self.layers * 2 * Hkv * D * 2
         i = sched.prefill_schedule(views, req.prompt_len, transfer, self.link, self.ttft_slo, self.cm)
-        if i < 0:  # no feasible instance: the paper's experiments still place the request; take the shortest queue
+        if i < 0:  # no feasible instance: the paper's experiments still place the request (Sec. 3.4); here it
+            # goes to the shortest prefill queue among the instances that can prefill at all
             self.stats["infeasible"] += 1
-            i = min(range(len(self.inst)), key=lambda j: (sum(r.prompt_len - r.done for r in self.inst[j].queue), j))
+            able = [j for j, v in enumerate(views) if v["chunk"] > v["batch_decodes"]] or list(range(len(self.inst)))
+            i = min(able, key=lambda j: (sum(r.prompt_len - r.done for r in self.inst[j].queue), j))
         x = self.inst[i]
         x.queue.append(req)
-        x.clock = max(x.clock, now)
-        req.where = i
+        req.where, req.ready = i, now
         req.route.append((now, "prefill", i))
 
     # ---- KV migration between instances' pools
@@ -191,7 +225,7 @@ class Cluster:
         nbytes = self.layers * ((kv + BLOCK - 1) // BLOCK) * 2 * Hkv * BLOCK * D * 2
         old = req.blocks
         req.blocks = []
-        dst.ensure_blocks(req, kv)
+        dst.reserve(req)
         if not self.dry:
             one = (np.array([0, 1], np.int32), np.array([kv - 1], np.int32))
             plan_s = Plan(src.pools[0], one[0], one[1], np.array([old], np.int32))
@@ -207,9 +241,8 @@ class Cluster:
         if req in src.decodes:
             src.decodes.remove(req)
         dst.decodes.append(req)
-        dst.clock = max(dst.clock, now + nbytes / self.link)
-        req.where = dst.index
-        req.decode_start_time, req.decode_start_done = max(now, dst.clock), req.done  # treated as a new decode request
+        req.where, req.ready = dst.index, now + nbytes / self.link  # the copy is asynchronous: only this request waits
+        req.decode_start_time, req.decode_start_done = req.ready, req.done  # treated as a new decode request
         req.route.append((now, why, dst.index))
         self.stats["bytes_moved"] += nbytes
 
@@ -233,12 +266,13 @@ class Cluster:
             else:
                 self.migrate(r, self.inst[j], now, "handoff")
                 self.stats["handoffs"] += 1
-        reqs = [((now - r.decode_start_time) / max(r.current_output_len, 1) if r.current_output_len else 0.0,
-                 r.current_output_len, len(r.blocks)) for r in x.decodes]
+        here = [r for r in x.decodes if r.ready <= now]  # a KV cache still in flight cannot move again
+        reqs = [((now - r.decode_start_time) / r.current_output_len if r.current_output_len else 0.0,
+                 r.current_output_len, len(r.blocks)) for r in here]
         picked = sched.decode_schedule(x.kind, reqs, self.tpot_slo, self.alpha, x.blocks_used,
                                        int(self.watermark_frac * x.num_blocks))
         want = sched.D_HEAVY if x.kind == sched.P_HEAVY else sched.P_HEAVY
-        for r in [x.decodes[i] for i in picked]:
+        for r in [here[i] for i in picked]:
             j = self._pick(want, (r.n_positions + BLOCK - 1) // BLOCK)
             if j < 0:
                 continue
@@ -255,14 +289,14 @@ class Cluster:
         done = []
         for _ in range(max_iterations):
             busy = [x for x in self.inst if x.has_work()]
-            t_next = min((x.clock for x in busy), default=None)
+            t_next = min((x.next_time() for x in busy), default=None)
             if pending and (t_next is None or pending[0].arrival <= t_next):
                 r = pending.pop(0)
                 self.admit(r, r.arrival)
                 continue
             if not busy:
                 break
-            x = min(busy, key=lambda y: (y.clock, y.index))
+            x = min(busy, key=lambda y: (y.next_time(), y.index))
             prefilled, finished = x.step(self.cm)
             done += finished
             self.after_step(x, prefilled)

@@ -72,6 +72,21 @@ def time_batch(b, steps, warmup=5):
     return float(np.median([a.elapsed_time(c) for a, c in ev])) * 1e3
 
 
+def fit_cost_model(cells):
+    """Non-negative least squares of step time = t_fixed + t_pair * pairs + t_kv_token * decode_ctx_tokens
+    (seconds, one layer) — the per-iteration form of Estimate(len, chunk, batch) in tc_sched.h.  The model is
+    additive, so it overestimates iterations in which a small chunk hides under the decode branch."""
+    from scipy.optimize import nnls
+    A = np.array([[1.0, c["pairs"], c["decode_ctx_tokens"]] for c in cells])
+    y = np.array([c["step_us"] * 1e-6 for c in cells])
+    scale = A.max(axis=0)
+    x, _ = nnls(A / scale, y)
+    x = x / scale
+    err = np.abs(A @ x - y) / y
+    return {"t_fixed": float(x[0]), "t_token": 0.0, "t_pair": float(x[1]), "t_kv_token": float(x[2]),
+            "max_rel_err": float(err.max())}
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--chunks", default="128,256,512,1024,2048")
@@ -82,6 +97,8 @@ def main():
     ap.add_argument("--steps", type=int, default=30)
     ap.add_argument("--seed", type=int, default=20250801)
     ap.add_argument("--json", action="store_true", help="also print one JSON line with all cells")
+    ap.add_argument("--fit", action="store_true",
+                    help="fit the additive per-layer cost model of the scheduling core (tc_sched.h) to the measured cells")
     a = ap.parse_args()
     Hq, Hkv, D = (int(x) for x in a.heads.split(","))
     lo, hi = (int(x) for x in a.decode_ctx.split(","))
@@ -95,13 +112,19 @@ def main():
         base = time_batch(b0, a.steps)
         b0["plan"].destroy()
         print(f"{n:8d} {0:6d} {base:9.1f} {base:15.1f} {0.0:16.1f} {0.0:18.3g}", flush=True)
-        cells.append({"decodes": n, "chunk": 0, "step_us": base})
+        cells.append({"decodes": n, "chunk": 0, "step_us": base, "pairs": 0, "decode_ctx_tokens": int(ctx_d.sum())})
         for C in chunks:
             b = build(Hq, Hkv, D, [C] + [1] * n, [a.chunk_offset] + list(ctx_d), a.seed)
             t = time_batch(b, a.steps)
             b["plan"].destroy()
             print(f"{n:8d} {C:6d} {t:9.1f} {base:15.1f} {t - base:16.1f} {C / (t * 1e-6):18.3g}", flush=True)
-            cells.append({"decodes": n, "chunk": C, "step_us": t})
+            cells.append({"decodes": n, "chunk": C, "step_us": t, "pairs": C * a.chunk_offset + C * (C + 1) // 2,
+                          "decode_ctx_tokens": int(ctx_d.sum())})
+    if a.fit:
+        cm = fit_cost_model(cells)
+        print("# additive cost model per layer (attention path only; t_token, the linear layers' share, is not measured here):")
+        print(f"#   t_fixed = {cm['t_fixed']:.3e} s   t_pair = {cm['t_pair']:.3e} s   t_kv_token = {cm['t_kv_token']:.3e} s"
+              f"   (largest relative error over the cells {cm['max_rel_err']:.1%})")
     if a.json:
         print(json.dumps({"heads": [Hq, Hkv, D], "chunk_offset": a.chunk_offset, "decode_ctx": [lo, hi], "cells": cells}))
 

@@ -17,7 +17,7 @@ def scenario(dry):
     # one prefill-heavy instance (chunk 64) and two decode-heavy ones (chunk 16), small pools so that the
     # memory watermark is reached and decodes flow
     cl = Cluster([sched.P_HEAVY, sched.D_HEAVY, sched.D_HEAVY], [64, 16, 16], [48, 12, 12], SHAPE, LAYERS, cm,
-                 tpot_slo=120e-6, ttft_slo=1e-3, watermark_frac=0.75, dry=dry)
+                 tpot_slo=80e-6, ttft_slo=1e-3, watermark_frac=0.75, dry=dry)
     rng = np.random.default_rng(3)
     reqs, t = [], 0.0
     for i in range(12):
