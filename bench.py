@@ -165,6 +165,8 @@ def main():
     ap.add_argument("--steps", type=int, default=200)
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--workload", default="prefill_heavy", choices=WORKLOADS + [MIGRATE])
+    ap.add_argument("--dtype", default="bf16", choices=["bf16", "fp16"],
+                    help="element type of the tensors (bf16 is the headline; fp16 is the precision the paper ran in)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cold", action="store_true",
                     help="overwrite a 1 GiB scratch buffer before every step so that nothing of the batch is left in "
@@ -197,6 +199,9 @@ def main():
         return
     idx = WORKLOADS.index(args.workload)
     spec = W.config_spec(idx)
+    if args.dtype != "bf16":
+        import dataclasses
+        spec = dataclasses.replace(spec, dtype=args.dtype)
     batch = W.make_batch(spec)
     work = W.algorithmic_work(spec)
     torch.cuda.set_device(0)
@@ -253,7 +258,7 @@ def main():
 
     line = {"metric": "mixed_batch_attention_tokens_per_s", "value": T / (ms_per_step * 1e-3), "unit": "tokens/s",
             "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
-            "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+            "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": args.dtype, "data": "synthetic",
             "config": {"workload": args.workload, "num_q_heads": spec.num_q_heads, "num_kv_heads": spec.num_kv_heads,
                        "head_dim": spec.head_dim, "block_size": spec.block_size, "num_seqs": spec.num_seqs,
                        "tokens": T, "prefill_chunk": int(spec.q_len.max()) if (spec.q_len > 1).any() else 0,

@@ -16,7 +16,7 @@
  * Every call returns a tc_status; nothing throws, aborts or prints.  After a
  * validation error nothing was launched.  Calls are asynchronous on `stream`.
  *
- * Tensor element type is bf16 (16-bit patterns).  Layouts, with B = block_size = 16,
+ * Tensor element type is bf16 or fp16 (16-bit patterns; tc_kv_pool.dtype).  Layouts, with B = block_size = 16,
  * D = head_dim, Hq / Hkv = query / KV heads, G = Hq / Hkv:
  *   q, out        [T][Hq][D]      packed query rows of the batch, T = q_start[num_seqs]
  *   k_new, v_new  [T][Hkv][D]     keys / values of the same rows
@@ -48,6 +48,7 @@ typedef enum {
 } tc_status;
 
 #define TC_BF16 1
+#define TC_FP16 2 /* IEEE half: the precision the paper's own experiments ran in (Sec. 4.1) */
 
 /* Shape of the paged KV pool and where it lives. */
 typedef struct {
@@ -55,7 +56,7 @@ typedef struct {
     int32_t num_kv_heads; /* Hkv */
     int32_t head_dim;     /* 64 or 128 */
     int32_t block_size;   /* 16 */
-    int32_t dtype;        /* TC_BF16 */
+    int32_t dtype;        /* TC_BF16 or TC_FP16: element type of q, k, v, out and the pools */
     int64_t num_blocks;   /* blocks in each pool, num_blocks * 16 < 2^31 */
     void *k_pool;         /* DEVICE [num_blocks][Hkv][D/8][16][8] bf16; may be NULL for tc_plan_create* */
     void *v_pool;         /* DEVICE [num_blocks][Hkv][D][16] bf16                                        */
@@ -135,8 +136,8 @@ tc_status tc_kv_append(const tc_plan *plan, const tc_kv_pool *pool, const void *
  * over j = 0..p of the row's sequence, read from the pool as it is when the kernel runs, so
  * tc_kv_append of the same batch must precede it on the same stream.  Prefill chunks and
  * decode tokens are processed by one kernel launch; sequences whose KV range was split get
- * their partial results combined by a small second launch.  fp32 accumulation, bf16 output
- * rounded to nearest even.  scale must be positive and finite.  q, out, workspace: DEVICE.  Results are bitwise reproducible
+ * their partial results combined by a small second launch.  fp32 accumulation; probabilities and
+ * the output are rounded to nearest even in the element type.  scale must be positive and finite.  q, out, workspace: DEVICE.  Results are bitwise reproducible
  * for a fixed plan. */
 tc_status tc_mixed_attention(const tc_plan *plan, const tc_kv_pool *pool, const void *q, void *out, float scale,
                              void *workspace, size_t workspace_bytes, void *stream);

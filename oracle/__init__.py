@@ -33,6 +33,9 @@ def lib():
                                        C.c_int64, C.c_int64, u16p]
         _lib.tco_kv_import.argtypes = [C.c_int, C.c_int, C.c_int, C.c_int64, C.c_int, pp, pp, i32p, C.c_int64,
                                        C.c_int64, C.c_int64, u16p]
+        _lib.tco_attention_dtype.argtypes = _lib.tco_attention.argtypes + [C.c_int]
+        _lib.tco_widen.argtypes = [C.c_uint16, C.c_int]
+        _lib.tco_widen.restype = C.c_double
         _lib.tco_num_threads.restype = C.c_int
     return _lib
 
@@ -138,8 +141,16 @@ def kv_import(k_pools, v_pools, num_kv_heads, head_dim, block_size, block_table,
             raise ValueError(f"oracle kv_import: block id outside the pool (rc={rc})")
 
 
+BF16, FP16 = 1, 2
+
+
+def widen(bits, dtype=BF16):
+    """Exact float64 value of one 16-bit pattern (bf16 or IEEE half)."""
+    return float(lib().tco_widen(int(bits), int(dtype)))
+
+
 def attention(k_pool, v_pool, num_q_heads, num_kv_heads, head_dim, block_size, q_start, ctx_len, block_table,
-              q, scale, rows=None):
+              q, scale, rows=None, dtype=BF16):
     """softmax(scale * q K^T) V over tokens 0..p of the query's own sequence, fp64.
     Returns float64 [n_rows][Hq][D] for the packed query rows in ``rows`` (default: all)."""
     q_start, ctx_len = _c(q_start, np.int32), _c(ctx_len, np.int32)
@@ -153,10 +164,10 @@ def attention(k_pool, v_pool, num_q_heads, num_kv_heads, head_dim, block_size, q
         rows = _c(rows, np.int32)
         n_rows, rows_p = len(rows), _p(rows, C.c_int32)
     out = np.empty((n_rows, num_q_heads, head_dim), np.float64)
-    rc = lib().tco_attention(num_q_heads, num_kv_heads, head_dim, block_size, nb, _p(k_pool, C.c_uint16),
-                             _p(v_pool, C.c_uint16), S, _p(q_start, C.c_int32), _p(ctx_len, C.c_int32),
-                             _p(table, C.c_int32), table.shape[1] if table.ndim == 2 else 0, _p(q, C.c_uint16),
-                             float(np.float32(scale)), rows_p, n_rows, _p(out, C.c_double))
+    rc = lib().tco_attention_dtype(num_q_heads, num_kv_heads, head_dim, block_size, nb, _p(k_pool, C.c_uint16),
+                                   _p(v_pool, C.c_uint16), S, _p(q_start, C.c_int32), _p(ctx_len, C.c_int32),
+                                   _p(table, C.c_int32), table.shape[1] if table.ndim == 2 else 0, _p(q, C.c_uint16),
+                                   float(np.float32(scale)), rows_p, n_rows, _p(out, C.c_double), int(dtype))
     if rc:
         raise ValueError(f"oracle attention rejected the batch (rc={rc})")
     return out
@@ -174,5 +185,6 @@ def run_batch(batch, rows=None, with_history=True):
     kv_append(k_pool, v_pool, sp.num_kv_heads, sp.head_dim, sp.block_size, batch.q_start, sp.ctx_len,
               batch.block_table, batch.k_new, batch.v_new)
     out = attention(k_pool, v_pool, sp.num_q_heads, sp.num_kv_heads, sp.head_dim, sp.block_size, batch.q_start,
-                    sp.ctx_len, batch.block_table, batch.q, sp.scale, rows)
+                    sp.ctx_len, batch.block_table, batch.q, sp.scale, rows,
+                    dtype=FP16 if getattr(sp, "dtype", "bf16") == "fp16" else BF16)
     return out, k_pool, v_pool

@@ -15,7 +15,7 @@
  *   - query head h reads KV head h / (Hq/Hkv) (grouped-query attention, cited in
  *     Sec. 2.2).
  *
- * Tensors are bf16 bit patterns (uint16_t) widened exactly to double.
+ * Tensors are bf16 (or, with dtype = 2, IEEE half) bit patterns (uint16_t) widened exactly to double.
  *
  * Pool layout (an interface shared with the GPU library by specification only;
  * B = block_size tokens per block, D = head_dim):
@@ -42,13 +42,35 @@ typedef struct {
     int64_t num_blocks;
 } shape_t;
 
-static double widen(uint16_t bits)
+#define TCO_BF16 1
+#define TCO_FP16 2
+
+/* bf16: the upper half of an IEEE single */
+static double widen_bf16(uint16_t bits)
 {
     uint32_t u = (uint32_t)bits << 16;
     float f;
     memcpy(&f, &u, sizeof f);
     return (double)f;
 }
+
+/* IEEE half: 1 sign, 5 exponent (bias 15), 10 fraction bits; the precision the paper's runs used (Sec. 4.1) */
+static double widen_fp16(uint16_t bits)
+{
+    int sign = bits >> 15, e = (bits >> 10) & 31, m = bits & 1023;
+    double v;
+    if (e == 0)
+        v = ldexp((double)m, -24); /* zero and subnormals */
+    else if (e == 31)
+        v = m ? NAN : INFINITY;
+    else
+        v = ldexp((double)(m + 1024), e - 25);
+    return sign ? -v : v;
+}
+
+static double widen_as(uint16_t bits, int dtype) { return dtype == TCO_FP16 ? widen_fp16(bits) : widen_bf16(bits); }
+
+double tco_widen(uint16_t bits, int dtype) { return widen_as(bits, dtype); }
 
 static int64_t k_index(const shape_t *sh, int64_t blk, int h, int tok, int d)
 {
@@ -199,10 +221,10 @@ int tco_kv_import(int Hkv, int D, int B, int64_t num_blocks, int L, uint16_t *co
  *   s_j = scale * sum_d q_d k_{j,d}   (j = 0..p, the token itself included)
  *   m = max_j s_j ; e_j = exp(s_j - m) ; out_d = sum_j e_j v_{j,d} / sum_j e_j
  */
-int tco_attention(int Hq, int Hkv, int D, int B, int64_t num_blocks, const uint16_t *k_pool,
-                  const uint16_t *v_pool, int S, const int32_t *q_start, const int32_t *ctx_len,
-                  const int32_t *table, int max_blocks, const uint16_t *q, double scale,
-                  const int32_t *rows, int64_t n_rows, double *out)
+int tco_attention_dtype(int Hq, int Hkv, int D, int B, int64_t num_blocks, const uint16_t *k_pool,
+                        const uint16_t *v_pool, int S, const int32_t *q_start, const int32_t *ctx_len,
+                        const int32_t *table, int max_blocks, const uint16_t *q, double scale,
+                        const int32_t *rows, int64_t n_rows, double *out, int dtype)
 {
     shape_t sh = {Hq, Hkv, D, B, num_blocks};
     if (Hkv <= 0 || Hq % Hkv) return -2;
@@ -244,7 +266,7 @@ int tco_attention(int Hq, int Hkv, int D, int B, int64_t num_blocks, const uint1
             int64_t blk = trow[j / B];
             int tok = (int)(j % B);
             double acc = 0.0;
-            for (int d = 0; d < D; d++) acc += widen(qv[d]) * widen(k_pool[k_index(&sh, blk, kvh, tok, d)]);
+            for (int d = 0; d < D; d++) acc += widen_as(qv[d], dtype) * widen_as(k_pool[k_index(&sh, blk, kvh, tok, d)], dtype);
             score[j] = scale * acc;
             if (score[j] > m) m = score[j];
         }
@@ -255,11 +277,21 @@ int tco_attention(int Hq, int Hkv, int D, int B, int64_t num_blocks, const uint1
             int tok = (int)(j % B);
             double e = exp(score[j] - m);
             denom += e;
-            for (int d = 0; d < D; d++) o[d] += e * widen(v_pool[v_index(&sh, blk, kvh, tok, d)]);
+            for (int d = 0; d < D; d++) o[d] += e * widen_as(v_pool[v_index(&sh, blk, kvh, tok, d)], dtype);
         }
         for (int d = 0; d < D; d++) o[d] /= denom;
         free(score);
     }
     free(owner);
     return bad ? -3 : 0;
+}
+
+/* The bf16 case under its original name. */
+int tco_attention(int Hq, int Hkv, int D, int B, int64_t num_blocks, const uint16_t *k_pool,
+                  const uint16_t *v_pool, int S, const int32_t *q_start, const int32_t *ctx_len,
+                  const int32_t *table, int max_blocks, const uint16_t *q, double scale,
+                  const int32_t *rows, int64_t n_rows, double *out)
+{
+    return tco_attention_dtype(Hq, Hkv, D, B, num_blocks, k_pool, v_pool, S, q_start, ctx_len, table, max_blocks, q,
+                               scale, rows, n_rows, out, TCO_BF16);
 }

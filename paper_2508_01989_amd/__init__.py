@@ -14,7 +14,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libtc_mi355x.so")
 
 TC_OK, TC_ERR_NULL, TC_ERR_SHAPE, TC_ERR_SPAN, TC_ERR_BLOCK, TC_ERR_WORKSPACE, TC_ERR_DEVICE, TC_ERR_ARG = range(8)
-TC_BF16 = 1
+TC_BF16, TC_FP16 = 1, 2
 
 EXPORTS = ["tc_plan_create", "tc_plan_create_host", "tc_plan_get_info", "tc_plan_copy_items",
            "tc_plan_workspace_bytes", "tc_plan_destroy", "tc_kv_append", "tc_mixed_attention", "tc_kv_gather",

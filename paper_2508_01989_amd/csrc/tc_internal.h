@@ -38,6 +38,7 @@ void set_error(const std::string &msg);
 
 struct tc_plan {
     int Hq = 0, Hkv = 0, D = 0, G = 0;
+    int dtype = TC_BF16;  // element type of q / k / v / out: selects the MFMA instantiation
     int64_t num_blocks = 0;
     int S = 0, T = 0;
     int n_prefill_seqs = 0, n_decode_seqs = 0;

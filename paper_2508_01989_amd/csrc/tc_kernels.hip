@@ -28,8 +28,28 @@
 
 namespace tc {
 
-typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
-typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
+typedef float f32x4_t __attribute__((ext_vector_type(4)));
+typedef float f32x16_t __attribute__((ext_vector_type(16)));
+
+// The two 16-bit element types the attention kernels are instantiated for.  Everything that depends
+// on the type is here: the vector types, the two MFMA shapes, and (through the casts to `t`) the
+// round-to-nearest-even conversions of probabilities and outputs.
+struct Bf16 {
+    typedef __bf16 t;
+    typedef __bf16 x8 __attribute__((ext_vector_type(8)));
+    typedef __bf16 x4 __attribute__((ext_vector_type(4)));
+    typedef __bf16 x2 __attribute__((ext_vector_type(2)));
+    static __device__ __forceinline__ f32x16_t mfma32(x8 a, x8 b, f32x16_t c) { return __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c, 0, 0, 0); }
+    static __device__ __forceinline__ f32x4_t mfma16(x8 a, x8 b, f32x4_t c) { return __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, b, c, 0, 0, 0); }
+};
+struct Fp16 {
+    typedef _Float16 t;
+    typedef _Float16 x8 __attribute__((ext_vector_type(8)));
+    typedef _Float16 x4 __attribute__((ext_vector_type(4)));
+    typedef _Float16 x2 __attribute__((ext_vector_type(2)));
+    static __device__ __forceinline__ f32x16_t mfma32(x8 a, x8 b, f32x16_t c) { return __builtin_amdgcn_mfma_f32_32x32x16_f16(a, b, c, 0, 0, 0); }
+    static __device__ __forceinline__ f32x4_t mfma16(x8 a, x8 b, f32x4_t c) { return __builtin_amdgcn_mfma_f32_16x16x32_f16(a, b, c, 0, 0, 0); }
+};
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
@@ -312,9 +332,12 @@ __device__ __forceinline__ float half_swap_sum(float v) {
     return __uint_as_float(r[0]) + __uint_as_float(r[1]);
 }
 
-template <int D>
+template <int D, class E>
 __device__ void prefill_item(const AttnArgs &A, const int32_t *__restrict__ it, const int32_t *__restrict__ pc, char *lds) {
     using C = PrefillCfg<D>;
+    using x8 = typename E::x8;
+    using x4 = typename E::x4;
+    using el = typename E::t;
     constexpr int KS = D / 16;  // k-steps of the QK^T product
     constexpr int MT = D / 32;  // 32-row tiles of O^T
     const int lane = threadIdx.x & 63;
@@ -340,9 +363,9 @@ __device__ void prefill_item(const AttnArgs &A, const int32_t *__restrict__ it, 
     const float c_log2 = A.scale_log2;
     const int v_lane_off = n * 32 + ((hh ^ ((n >> 3) & 1)) * 16);  // this lane's 16 bytes inside a 32-row V^T tile
 
-    bf16x8 qreg[KS];
+    x8 qreg[KS];
 #pragma unroll
-    for (int kk = 0; kk < KS; kk++) qreg[kk] = *reinterpret_cast<const bf16x8 *>(A.q + row_off + (2 * kk + hh) * 8);
+    for (int kk = 0; kk < KS; kk++) qreg[kk] = *reinterpret_cast<const x8 *>(A.q + row_off + (2 * kk + hh) * 8);
 
     f32x16 o[MT];
 #pragma unroll
@@ -356,9 +379,9 @@ __device__ void prefill_item(const AttnArgs &A, const int32_t *__restrict__ it, 
 #pragma unroll
     for (int r = 0; r < 16; r++) lsum[r] = 0.f;
     float l_run = 0.f;
-    bf16x8 ones;
+    x8 ones;
 #pragma unroll
-    for (int e = 0; e < 8; e++) ones[e] = (__bf16)1.0f;
+    for (int e = 0; e < 8; e++) ones[e] = (el)1.0f;
 
     int page_id = prefill_page_id<D>(pages, n_pages, t_begin, wave);
     prefill_fetch<D>(A, kvh, page_id, lds, lds + 2 * C::kTileBytes, wave, lane);
@@ -387,8 +410,8 @@ __device__ void prefill_item(const AttnArgs &A, const int32_t *__restrict__ it, 
                 const char *kp = ks + (2 * mt + (n >> 4)) * C::kPageBytes + (n & 15) * 16;
 #pragma unroll
                 for (int kk = 0; kk < KS; kk++) {
-                    const bf16x8 a = *reinterpret_cast<const bf16x8 *>(kp + (2 * kk + hh) * (kBlock * 16));
-                    s[mt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qreg[kk], s[mt], 0, 0, 0);
+                    const x8 a = *reinterpret_cast<const x8 *>(kp + (2 * kk + hh) * (kBlock * 16));
+                    s[mt] = E::mfma32(a, qreg[kk], s[mt]);
                 }
             }
             if (tok0 + C::kTileTokens - 1 > wave_pmin) {  // the diagonal crosses this tile: causal mask
@@ -433,14 +456,14 @@ __device__ void prefill_item(const AttnArgs &A, const int32_t *__restrict__ it, 
             if (!kRowSumOnMfma) l_run += psum;
 #pragma unroll
             for (int b = 0; b < C::kTilePages; b++) {
-                bf16x8 pb;
+                x8 pb;
 #pragma unroll
-                for (int e = 0; e < 8; e++) pb[e] = (__bf16)s[b >> 1][8 * (b & 1) + e];
-                if (kRowSumOnMfma) lsum = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ones, pb, lsum, 0, 0, 0);
+                for (int e = 0; e < 8; e++) pb[e] = (el)s[b >> 1][8 * (b & 1) + e];
+                if (kRowSumOnMfma) lsum = E::mfma32(ones, pb, lsum);
 #pragma unroll
                 for (int c = 0; c < MT; c++) {
-                    const bf16x8 a = *reinterpret_cast<const bf16x8 *>(vs + b * C::kPageBytes + c * (32 * 32) + v_lane_off);
-                    o[c] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, pb, o[c], 0, 0, 0);
+                    const x8 a = *reinterpret_cast<const x8 *>(vs + b * C::kPageBytes + c * (32 * 32) + v_lane_off);
+                    o[c] = E::mfma32(a, pb, o[c]);
                 }
             }
         }
@@ -477,10 +500,10 @@ __device__ void prefill_item(const AttnArgs &A, const int32_t *__restrict__ it, 
         for (int c = 0; c < MT; c++)
 #pragma unroll
             for (int q4 = 0; q4 < 4; q4++) {
-                bf16x4 w;
+                x4 w;
 #pragma unroll
-                for (int e = 0; e < 4; e++) w[e] = (__bf16)(o[c][4 * q4 + e] * inv);
-                *reinterpret_cast<bf16x4 *>(A.out + row_off + 32 * c + 8 * q4 + 4 * hh) = w;
+                for (int e = 0; e < 4; e++) w[e] = (el)(o[c][4 * q4 + e] * inv);
+                *reinterpret_cast<x4 *>(A.out + row_off + 32 * c + 8 * q4 + 4 * hh) = w;
             }
     }
 }
@@ -518,10 +541,12 @@ __device__ __forceinline__ void decode_fetch(const AttnArgs &A, int kvh, int id0
     }
 }
 
-template <int D>
-__device__ __forceinline__ void decode_consume(const AttnArgs &A, DecodeStage<D> &st, const bf16x8 (&qreg)[D / 32],
+template <int D, class E>
+__device__ __forceinline__ void decode_consume(const AttnArgs &A, DecodeStage<D> &st, const typename E::x8 (&qreg)[D / 32],
                                                int n_valid0, int n_valid1, int g, f32x4 (&o)[D / 16], float &m_run,
                                                float &l_run) {
+    using x8 = typename E::x8;
+    using el = typename E::t;
     constexpr int KS = D / 32, MT = D / 16;
     const int n_valid[2] = {n_valid0, n_valid1};
     f32x4 s[2];
@@ -530,7 +555,7 @@ __device__ __forceinline__ void decode_consume(const AttnArgs &A, DecodeStage<D>
         s[b] = f32x4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
         for (int kk = 0; kk < KS; kk++)
-            s[b] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, st.k[b][kk]), qreg[kk], s[b], 0, 0, 0);
+            s[b] = E::mfma16(__builtin_bit_cast(x8, st.k[b][kk]), qreg[kk], s[b]);
     }
     if (n_valid1 < kBlock) {  // the split ends inside this pair: mask scores, make V finite
 #pragma unroll
@@ -555,7 +580,7 @@ __device__ __forceinline__ void decode_consume(const AttnArgs &A, DecodeStage<D>
     const float m_new = fmaxf(m_run, mx * A.scale_log2);
     const float alpha = fast_exp2(m_run - m_new);
     m_run = m_new;
-    bf16x8 pb;
+    x8 pb;
     float psum = 0.f;
 #pragma unroll
     for (int b = 0; b < 2; b++)
@@ -563,19 +588,22 @@ __device__ __forceinline__ void decode_consume(const AttnArgs &A, DecodeStage<D>
         for (int r = 0; r < 4; r++) {
             const float pv = fast_exp2(__builtin_fmaf(s[b][r], A.scale_log2, -m_new));
             psum += pv;
-            pb[4 * b + r] = (__bf16)pv;
+            pb[4 * b + r] = (el)pv;
         }
     l_run = l_run * alpha + psum;
 #pragma unroll
     for (int c = 0; c < MT; c++) {
         o[c] *= alpha;
         const u32x4 aw = {st.v[0][c][0], st.v[0][c][1], st.v[1][c][0], st.v[1][c][1]};
-        o[c] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, aw), pb, o[c], 0, 0, 0);
+        o[c] = E::mfma16(__builtin_bit_cast(x8, aw), pb, o[c]);
     }
 }
 
-template <int D>
+template <int D, class E>
 __device__ void decode_item(const AttnArgs &A, const int32_t *__restrict__ it) {
+    using x8 = typename E::x8;
+    using x4 = typename E::x4;
+    using el = typename E::t;
     constexpr int KS = D / 32;  // k-steps of K Q^T
     constexpr int MT = D / 16;  // 16-row tiles of O^T
     const int lane = threadIdx.x & 63;
@@ -588,13 +616,13 @@ __device__ void decode_item(const AttnArgs &A, const int32_t *__restrict__ it) {
     const int32_t *pages = A.pages + it[DC_PAGEOFF] + page0;
     const int my_page = pages[min(lane, n_pg - 1)];  // lane i holds the id of page i of the split
 
-    bf16x8 qreg[KS];
+    x8 qreg[KS];
     const int64_t q_off = ((int64_t)qrow * A.Hq + kvh * G + min(j, G - 1)) * D;
 #pragma unroll
     for (int kk = 0; kk < KS; kk++) {
         u32x4 w = *reinterpret_cast<const u32x4 *>(A.q + q_off + (4 * kk + g) * 8);
         if (j >= G) w = u32x4{0u, 0u, 0u, 0u};
-        qreg[kk] = __builtin_bit_cast(bf16x8, w);
+        qreg[kk] = __builtin_bit_cast(x8, w);
     }
 
     f32x4 o[MT];
@@ -611,12 +639,12 @@ __device__ void decode_item(const AttnArgs &A, const int32_t *__restrict__ it) {
         if (pp + 2 < n_pg)
             decode_fetch<D>(A, kvh, __builtin_amdgcn_readlane(my_page, pp + 2),
                             __builtin_amdgcn_readlane(my_page, min(pp + 3, last)), j, g, sb);
-        decode_consume<D>(A, sa, qreg, n_tok - pp * kBlock, n_tok - (pp + 1) * kBlock, g, o, m_run, l_run);
+        decode_consume<D, E>(A, sa, qreg, n_tok - pp * kBlock, n_tok - (pp + 1) * kBlock, g, o, m_run, l_run);
         if (pp + 2 < n_pg) {
             if (pp + 4 < n_pg)
                 decode_fetch<D>(A, kvh, __builtin_amdgcn_readlane(my_page, pp + 4),
                                 __builtin_amdgcn_readlane(my_page, min(pp + 5, last)), j, g, sa);
-            decode_consume<D>(A, sb, qreg, n_tok - (pp + 2) * kBlock, n_tok - (pp + 3) * kBlock, g, o, m_run, l_run);
+            decode_consume<D, E>(A, sb, qreg, n_tok - (pp + 2) * kBlock, n_tok - (pp + 3) * kBlock, g, o, m_run, l_run);
         }
     }
     l_run += xor_lanes(l_run, 16);
@@ -627,10 +655,10 @@ __device__ void decode_item(const AttnArgs &A, const int32_t *__restrict__ it) {
         uint16_t *dst = A.out + ((int64_t)qrow * A.Hq + kvh * G + j) * D + 4 * g;
 #pragma unroll
         for (int c = 0; c < MT; c++) {
-            bf16x4 w;
+            x4 w;
 #pragma unroll
-            for (int e = 0; e < 4; e++) w[e] = (__bf16)(o[c][e] * inv);
-            *reinterpret_cast<bf16x4 *>(dst + 16 * c) = w;
+            for (int e = 0; e < 4; e++) w[e] = (el)(o[c][e] * inv);
+            *reinterpret_cast<x4 *>(dst + 16 * c) = w;
         }
     } else {
         float *dst = A.ws_o + ((int64_t)slot * G + j) * D + 4 * g;
@@ -653,7 +681,7 @@ struct AttnScalars {
 // The pointers are separate __restrict__ kernel arguments (not struct members) so that the
 // compiler knows the work list and the page table are never written and can fetch them with
 // scalar loads.
-template <int D>
+template <int D, class E>
 __global__ void __launch_bounds__(kWgThreads, kWgPerCu)
     mixed_attention_kernel(const uint16_t *__restrict__ k_pool, const uint16_t *__restrict__ v_pool,
                            const uint16_t *__restrict__ q, uint16_t *__restrict__ out, const int32_t *__restrict__ pages,
@@ -668,11 +696,11 @@ __global__ void __launch_bounds__(kWgThreads, kWgPerCu)
     A.scale_log2 = sc.scale_log2;
     if ((int)blockIdx.x < A.n_prefill) {
         const int32_t *pc = pieces + (int64_t)blockIdx.x * kItemInts;
-        prefill_item<D>(A, prefill + (int64_t)pc[PP_ITEM] * kItemInts, pc, lds);
+        prefill_item<D, E>(A, prefill + (int64_t)pc[PP_ITEM] * kItemInts, pc, lds);
     } else {
         const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
         const int idx = ((int)blockIdx.x - A.n_prefill) * kWgWaves + wave;
-        if (idx < A.n_decode) decode_item<D>(A, decode + (int64_t)idx * kItemInts);
+        if (idx < A.n_decode) decode_item<D, E>(A, decode + (int64_t)idx * kItemInts);
     }
 }
 
@@ -682,35 +710,35 @@ __global__ void __launch_bounds__(kWgThreads, kWgPerCu)
 // head-dim elements, so each partial row is one coalesced read.  Lane i first fetches (m_i, l_i) of
 // split i (at most 64 splits per wave pass), the wave reduces the maximum, and the weighted sum runs
 // over the splits, in index order, with the weights broadcast from those registers.
-template <int D>
+template <int D, class E>
 __global__ void __launch_bounds__(256) split_merge_kernel(const int32_t *__restrict__ items, const float *__restrict__ ws_o,
                                                           const float *__restrict__ ws_ml, uint16_t *__restrict__ out,
                                                           int Hq, int G) {
-    constexpr int E = D / 64;  // elements per lane
+    constexpr int NE = D / 64;  // elements per lane
     const int32_t *it = items + (int64_t)blockIdx.x * kItemInts;
     const int kvh = it[MG_KVH], qrow = it[MG_QROW], slot0 = it[MG_SLOT0], ns = it[MG_NSPLIT];
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     for (int j = wave; j < G; j += 4) {
-        float acc[E];
+        float acc[NE];
 #pragma unroll
-        for (int e = 0; e < E; e++) acc[e] = 0.f;
+        for (int e = 0; e < NE; e++) acc[e] = 0.f;
         float m_star = -1e30f, den = 0.f;
         for (int base = 0; base < ns; base += 64) {  // 64 splits per pass; passes chained by an online rescale
             const int n = min(64, ns - base);
-            const float *src = ws_o + ((int64_t)(slot0 + base) * G + j) * D + lane * E;
+            const float *src = ws_o + ((int64_t)(slot0 + base) * G + j) * D + lane * NE;
             // Partial rows are fetched kChunk at a time, all loads of a chunk in flight together; the
             // first chunk is requested before the weights are known.
             constexpr int kChunk = 8;
-            float row[kChunk][E];
+            float row[kChunk][NE];
             auto fetch = [&](int c0) {
 #pragma unroll
                 for (int u = 0; u < kChunk; u++)
                     if (c0 + u < n) {
                         const float *r = src + (int64_t)(c0 + u) * G * D;
-                        if (E == 2) {
+                        if (NE == 2) {
                             const float2 v = *reinterpret_cast<const float2 *>(r);
                             row[u][0] = v.x;
-                            row[u][E - 1] = v.y;
+                            row[u][NE - 1] = v.y;
                         } else {
                             row[u][0] = r[0];
                         }
@@ -732,28 +760,27 @@ __global__ void __launch_bounds__(256) split_merge_kernel(const int32_t *__restr
             for (int sh = 1; sh < 64; sh *= 2) wl += xor_lanes(wl, sh);
             den = den * rescale + wl;
 #pragma unroll
-            for (int e = 0; e < E; e++) acc[e] *= rescale;
+            for (int e = 0; e < NE; e++) acc[e] *= rescale;
             for (int c0 = 0; c0 < n; c0 += kChunk) {
 #pragma unroll
                 for (int u = 0; u < kChunk; u++)
                     if (c0 + u < n) {
                         const float w = __shfl(w_i, c0 + u, 64);
 #pragma unroll
-                        for (int e = 0; e < E; e++) acc[e] += w * row[u][e];
+                        for (int e = 0; e < NE; e++) acc[e] += w * row[u][e];
                     }
                 if (c0 + kChunk < n) fetch(c0 + kChunk);
             }
         }
         const float inv = 1.f / den;
-        uint16_t *dst = out + ((int64_t)qrow * Hq + kvh * G + j) * D + lane * E;
-        if (E == 2) {
-            typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
-            bf16x2 w2;
-            w2[0] = (__bf16)(acc[0] * inv);
-            w2[1] = (__bf16)(acc[E - 1] * inv);
-            *reinterpret_cast<bf16x2 *>(dst) = w2;
+        uint16_t *dst = out + ((int64_t)qrow * Hq + kvh * G + j) * D + lane * NE;
+        if (NE == 2) {
+            typename E::x2 w2;
+            w2[0] = (typename E::t)(acc[0] * inv);
+            w2[1] = (typename E::t)(acc[NE - 1] * inv);
+            *reinterpret_cast<typename E::x2 *>(dst) = w2;
         } else {
-            const __bf16 w1 = (__bf16)(acc[0] * inv);
+            const typename E::t w1 = (typename E::t)(acc[0] * inv);
             *dst = __builtin_bit_cast(uint16_t, w1);
         }
     }
@@ -833,24 +860,24 @@ int launch_kv_migrate(const tc_plan *p, bool import, int page0, int n_pages, int
     return 0;
 }
 
-template <int D>
+template <int D, class E>
 static int launch_attention_d(const tc_plan *p, const AttnArgs &A, hipStream_t st) {
     static bool lds_ok = false;  // opt in to more than 64 KiB of dynamic LDS once per process
     const int lds = PrefillCfg<D>::kLdsBytes;
     if (!lds_ok) {
-        hipError_t e = hipFuncSetAttribute((const void *)mixed_attention_kernel<D>, hipFuncAttributeMaxDynamicSharedMemorySize, lds);
+        hipError_t e = hipFuncSetAttribute((const void *)mixed_attention_kernel<D, E>, hipFuncAttributeMaxDynamicSharedMemorySize, lds);
         if (e != hipSuccess) return (int)e;
         lds_ok = true;
     }
     const int grid = p->grid_blocks();
     const AttnScalars sc = {A.n_prefill, A.n_decode, A.Hq, A.Hkv, A.G, A.scale_log2};
     if (grid > 0)
-        mixed_attention_kernel<D><<<grid, kWgThreads, p->n_pieces > 0 ? lds : 0, st>>>(A.k_pool, A.v_pool, A.q, A.out, A.pages, A.prefill,
+        mixed_attention_kernel<D, E><<<grid, kWgThreads, p->n_pieces > 0 ? lds : 0, st>>>(A.k_pool, A.v_pool, A.q, A.out, A.pages, A.prefill,
                                                                                 A.pieces, A.decode, A.ws_o, A.ws_ml, sc);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return (int)e;
     if (p->n_merge > 0)
-        split_merge_kernel<D><<<p->n_merge, 256, 0, st>>>(p->dev + p->off_merge, A.ws_o, A.ws_ml, A.out, A.Hq, A.G);
+        split_merge_kernel<D, E><<<p->n_merge, 256, 0, st>>>(p->dev + p->off_merge, A.ws_o, A.ws_ml, A.out, A.Hq, A.G);
     return (int)hipGetLastError();
 }
 
@@ -873,7 +900,9 @@ int launch_attention(const tc_plan *p, const tc_kv_pool *pool, const void *q, vo
     A.Hkv = p->Hkv;
     A.G = p->G;
     A.scale_log2 = scale * 1.4426950408889634f;
-    return p->D == 128 ? launch_attention_d<128>(p, A, (hipStream_t)stream) : launch_attention_d<64>(p, A, (hipStream_t)stream);
+    hipStream_t st = (hipStream_t)stream;
+    if (p->dtype == TC_FP16) return p->D == 128 ? launch_attention_d<128, Fp16>(p, A, st) : launch_attention_d<64, Fp16>(p, A, st);
+    return p->D == 128 ? launch_attention_d<128, Bf16>(p, A, st) : launch_attention_d<64, Bf16>(p, A, st);
 }
 
 }  // namespace tc

@@ -22,7 +22,7 @@ static tc_status fail(tc_status s, const std::string &msg) {
 tc_status check_pool_matches(const tc_plan *plan, const tc_kv_pool *pool, bool need_ptrs) {
     if (!plan || !pool) return fail(TC_ERR_NULL, "plan or pool is NULL");
     if (pool->num_q_heads != plan->Hq || pool->num_kv_heads != plan->Hkv || pool->head_dim != plan->D ||
-        pool->block_size != kBlock || pool->num_blocks != plan->num_blocks || pool->dtype != TC_BF16)
+        pool->block_size != kBlock || pool->num_blocks != plan->num_blocks || pool->dtype != plan->dtype)
         return fail(TC_ERR_SHAPE, "pool shape differs from the shape the plan was built for");
     if (need_ptrs && (!pool->k_pool || !pool->v_pool)) return fail(TC_ERR_NULL, "k_pool or v_pool is NULL");
     return TC_OK;
@@ -63,7 +63,7 @@ tc_status build_plan(const tc_kv_pool *pool, const tc_batch *b, tc_plan **out) {
     if (!pool || !b || !out) return fail(TC_ERR_NULL, "pool, batch or out is NULL");
     *out = nullptr;
     const int Hq = pool->num_q_heads, Hkv = pool->num_kv_heads, D = pool->head_dim;
-    if (pool->dtype != TC_BF16) return fail(TC_ERR_SHAPE, "dtype must be TC_BF16");
+    if (pool->dtype != TC_BF16 && pool->dtype != TC_FP16) return fail(TC_ERR_SHAPE, "dtype must be TC_BF16 or TC_FP16");
     if (pool->block_size != kBlock) return fail(TC_ERR_SHAPE, "block_size must be 16");
     if (D != 64 && D != 128) return fail(TC_ERR_SHAPE, "head_dim must be 64 or 128");
     if (Hkv <= 0 || Hq <= 0 || Hq % Hkv) return fail(TC_ERR_SHAPE, "num_q_heads must be a positive multiple of num_kv_heads");
@@ -80,7 +80,7 @@ tc_status build_plan(const tc_kv_pool *pool, const tc_batch *b, tc_plan **out) {
 
     tc_plan *p = new (std::nothrow) tc_plan();
     if (!p) return fail(TC_ERR_DEVICE, "out of host memory");
-    p->Hq = Hq; p->Hkv = Hkv; p->D = D; p->G = G; p->num_blocks = pool->num_blocks; p->S = S;
+    p->Hq = Hq; p->Hkv = Hkv; p->D = D; p->G = G; p->dtype = pool->dtype; p->num_blocks = pool->num_blocks; p->S = S;
     p->q_start.assign(S + 1, 0);
     p->ctx_len.assign(S, 0);
     p->page_off.assign(S + 1, 0);

@@ -7,7 +7,7 @@ from __future__ import annotations
 import numpy as np
 import torch
 
-from . import Plan, make_pool, tc_kv_append, tc_kv_gather, tc_mixed_attention
+from . import TC_BF16, TC_FP16, Plan, make_pool, tc_kv_append, tc_kv_gather, tc_mixed_attention
 
 
 def to_dev(a: np.ndarray, device="cuda:0") -> torch.Tensor:
@@ -30,7 +30,9 @@ class DeviceBatch:
         fill = int(np.array([poison], np.uint16).view(np.int16)[0])
         self.k_pool = torch.full((n,), fill, dtype=torch.int16, device=device)
         self.v_pool = torch.full((n,), fill, dtype=torch.int16, device=device)
-        self.pool = make_pool(sp.num_q_heads, sp.num_kv_heads, sp.head_dim, batch.num_blocks, self.k_pool, self.v_pool)
+        self.fp16 = getattr(sp, "dtype", "bf16") == "fp16"
+        self.pool = make_pool(sp.num_q_heads, sp.num_kv_heads, sp.head_dim, batch.num_blocks, self.k_pool, self.v_pool,
+                              dtype=TC_FP16 if self.fp16 else TC_BF16)
         self._append_history()
         self.q = to_dev(batch.q, device)
         self.k_new = to_dev(batch.k_new, device)
@@ -80,6 +82,8 @@ class DeviceBatch:
     def out_f64(self) -> np.ndarray:
         torch.cuda.synchronize()
         u = to_host(self.out)
+        if self.fp16:
+            return u.view(np.float16).astype(np.float64)
         return (u.astype(np.uint32) << np.uint32(16)).view(np.float32).astype(np.float64)
 
     def pools_host(self):

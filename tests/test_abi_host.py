@@ -91,6 +91,17 @@ def test_validation_status_codes(tc):
     L.tc_plan_destroy(None)
 
 
+def test_element_type_is_part_of_the_plan(tc):
+    p16 = _plan(tc, dtype=tc.TC_FP16)
+    pool_bf = tc.make_pool(8, 2, 128, 32, k_pool=4096, v_pool=4096)
+    pool_16 = tc.make_pool(8, 2, 128, 32, k_pool=4096, v_pool=4096, dtype=tc.TC_FP16)
+    assert _status(tc, lambda: tc.tc_kv_append(p16, pool_bf, 4096, 4096)) == tc.TC_ERR_SHAPE   # plan is fp16, pool says bf16
+    assert _status(tc, lambda: tc.tc_kv_append(p16, pool_16, 4096, 4096)) == tc.TC_ERR_ARG     # matches; host-only plan
+    with pytest.raises(tc.TcError) as e:
+        _plan(tc, dtype=3)
+    assert e.value.status == tc.TC_ERR_SHAPE
+
+
 def test_host_only_plan_cannot_be_launched(tc):
     p = _plan(tc)
     pool = tc.make_pool(8, 2, 128, 32, k_pool=4096, v_pool=4096)

@@ -90,6 +90,28 @@ def test_small_cases_match_oracle(H, name):
     assert (db.plan.info.num_prefill_pieces > db.plan.info.num_prefill_items) == name.startswith("cut_")
 
 
+# IEEE half, the precision the paper's own runs used (Sec. 4.1): 11 significant bits instead of 8, so
+# the same kernels must land well inside the bf16 tolerance; the bounds below are 5x tighter.
+FP16_MAX_ABS, FP16_REL_L2 = 2e-3, 1e-3
+FP16_CASES = ["decode_long_ragged", "prefill_offset_not_page_aligned", "two_prefill_segments_and_decodes", "gqa_g5",
+              "head_dim_64_gqa", "cut_small_chunk_long_context"]
+
+
+@pytest.mark.parametrize("name", FP16_CASES)
+def test_small_cases_match_oracle_in_half_precision(H, name):
+    Hq, Hkv, D, q_len, ctx = SMALL[name]
+    b = W.make_batch(W.custom_spec(name, Hq, Hkv, D, q_len, ctx, seed=zlib.crc32(name.encode()) % 10007, dtype="fp16"))
+    (mx, rel), _ = run_and_compare(H, b, name + " fp16")
+    assert mx <= FP16_MAX_ABS and rel <= FP16_REL_L2, (mx, rel)
+
+
+def test_config1_prefill_heavy_half_precision_sampled(H):
+    import dataclasses
+    b = W.make_batch(dataclasses.replace(W.config_spec(1), dtype="fp16"))
+    (mx, rel), _ = run_and_compare(H, b, "config1 prefill-heavy fp16 (sampled rows)", rows=stratified_rows(b, 61))
+    assert mx <= FP16_MAX_ABS and rel <= FP16_REL_L2, (mx, rel)
+
+
 def test_config0_tiny_full(H):
     b = W.make_batch(W.config_spec(0))
     (mx, rel), db = run_and_compare(H, b, "config0 tiny")

@@ -296,3 +296,40 @@ def test_gqa_head_mapping_is_consecutive_groups():
     assert np.array_equal(out[:, 0], out[:, 1]) and np.array_equal(out[:, 0], out[:, 2])
     assert np.array_equal(out[:, 3], out[:, 5])
     assert np.max(np.abs(out[:, 0] - out[:, 3])) > 1e-3
+
+
+# ----------------------------------------------------------------------------- IEEE half inputs
+def test_half_widening_matches_numpy_for_every_bit_pattern():
+    bits = np.arange(65536, dtype=np.uint32).astype(np.uint16)
+    want = bits.view(np.float16).astype(np.float64)
+    got = np.array([oracle.widen(int(b), oracle.FP16) for b in bits])
+    same = (got == want) | (np.isnan(got) & np.isnan(want))
+    assert same.all()
+    assert np.array_equal(np.signbit(got), np.signbit(want))
+    # and bf16 against the generator's own conversion, on a sample
+    sample = bits[::97]
+    sample = sample[(sample & 0x7F80) != 0x7F80]  # finite patterns
+    assert all(oracle.widen(int(b), oracle.BF16) == v for b, v in zip(sample, W.bf16_bits_to_f64(sample)))
+
+
+def test_half_precision_batch_matches_dense_brute_force():
+    b = W.make_batch(W.custom_spec("half", 4, 2, 16, (5, 1, 1, 19), (3, 0, 16, 14), seed=12, dtype="fp16"))
+    out, _, _ = oracle.run_batch(b)
+    sp = b.spec
+    G = sp.num_q_heads // sp.num_kv_heads
+    for s in range(sp.num_seqs):
+        k, v = W.contiguous_kv(b, s)
+        k, v = W.bits_to_f64(k, "fp16"), W.bits_to_f64(v, "fp16")
+        a, e = int(b.q_start[s]), int(b.q_start[s + 1])
+        q = W.bits_to_f64(b.q[a:e], "fp16")
+        for i in range(e - a):
+            p = int(sp.ctx_len[s]) + i
+            for h in range(sp.num_q_heads):
+                sc = float(np.float32(sp.scale)) * (k[:p + 1, h // G] @ q[i, h])
+                w = np.exp(sc - sc.max())
+                ref = (w / w.sum()) @ v[:p + 1, h // G]
+                assert np.allclose(out[a + i, h], ref, rtol=0, atol=1e-12)
+    # the same bit patterns read as bf16 give a different answer: the dtype switch is live
+    other = oracle.attention(*oracle.run_batch(b)[1:], sp.num_q_heads, sp.num_kv_heads, sp.head_dim, 16, b.q_start,
+                             sp.ctx_len, b.block_table, b.q, sp.scale, dtype=oracle.BF16)
+    assert not np.allclose(other, out, atol=1e-3)

@@ -29,6 +29,12 @@ def f32_to_bf16_bits(x: np.ndarray) -> np.ndarray:
     return (rounded >> np.uint32(16)).astype(np.uint16)
 
 
+def bits_to_f64(bits: np.ndarray, dtype: str = "bf16") -> np.ndarray:
+    """Exact float64 values of 16-bit patterns of either element type."""
+    bits = np.asarray(bits, np.uint16)
+    return bf16_bits_to_f64(bits) if dtype == "bf16" else bits.view(np.float16).astype(np.float64)
+
+
 def bf16_bits_to_f64(b: np.ndarray) -> np.ndarray:
     """Widen bf16 bit patterns to float64 (exact)."""
     b = np.ascontiguousarray(b, dtype=np.uint16)
@@ -49,6 +55,7 @@ class BatchSpec:
     pool_slack: float = 1.25   # pool holds ceil(pool_slack * used) blocks ...
     num_blocks: int | None = None  # ... unless the pool size is given outright
     seed: int = BASE_SEED
+    dtype: str = "bf16"        # element type of the tensors: "bf16", or "fp16" (the paper's own precision, Sec. 4.1)
 
     @property
     def scale(self) -> float:
@@ -105,10 +112,10 @@ def config_spec(index: int, seed: int | None = None) -> BatchSpec:
 
 
 def custom_spec(name, num_q_heads, num_kv_heads, head_dim, q_len, ctx_len, *, value_scale=1.0,
-                pool_slack=1.5, num_blocks=None, seed=BASE_SEED, block_size=16) -> BatchSpec:
+                pool_slack=1.5, num_blocks=None, seed=BASE_SEED, block_size=16, dtype="bf16") -> BatchSpec:
     return BatchSpec(name, num_q_heads, num_kv_heads, head_dim, block_size,
                      np.asarray(q_len, np.int32), np.asarray(ctx_len, np.int32), value_scale, pool_slack,
-                     num_blocks, seed)
+                     num_blocks, seed, dtype)
 
 
 @dataclass
@@ -158,9 +165,10 @@ def make_tables(spec: BatchSpec, rng) -> tuple[np.ndarray, int, int]:
     return table, max_blocks, num_blocks
 
 
-def _normal_bf16(seed_key, shape, value_scale, chunk=1 << 22) -> np.ndarray:
-    """N(0,1) * value_scale rounded to bf16.  Every chunk of 2^22 values has its own generator
-    keyed by (seed_key, chunk index), so the result does not depend on the worker count."""
+def _normal_bf16(seed_key, shape, value_scale, chunk=1 << 22, dtype="bf16") -> np.ndarray:
+    """N(0,1) * value_scale rounded to bf16 (or to IEEE half by numpy's own conversion).  Every chunk
+    of 2^22 values has its own generator keyed by (seed_key, chunk index), so the result does not
+    depend on the worker count."""
     n = int(np.prod(shape))
     out = np.empty(n, dtype=np.uint16)
 
@@ -169,7 +177,7 @@ def _normal_bf16(seed_key, shape, value_scale, chunk=1 << 22) -> np.ndarray:
         x = np.random.default_rng([*seed_key, ci]).standard_normal(b - a, dtype=np.float32)
         if value_scale != 1.0:
             x *= np.float32(value_scale)
-        out[a:b] = f32_to_bf16_bits(x)
+        out[a:b] = f32_to_bf16_bits(x) if dtype == "bf16" else x.astype(np.float16).view(np.uint16)
 
     n_chunks = (n + chunk - 1) // chunk
     if n_chunks <= 1:
@@ -192,11 +200,11 @@ def make_batch(spec: BatchSpec) -> Batch:
     hist_start[1:] = np.cumsum(spec.ctx_len.astype(np.int64))
     T, Hs = int(q_start[-1]), int(hist_start[-1])
     Hq, Hkv, D = spec.num_q_heads, spec.num_kv_heads, spec.head_dim
-    q = _normal_bf16((spec.seed, 1), (T, Hq, D), spec.value_scale)
-    k_new = _normal_bf16((spec.seed, 2), (T, Hkv, D), spec.value_scale)
-    v_new = _normal_bf16((spec.seed, 3), (T, Hkv, D), spec.value_scale)
-    k_hist = _normal_bf16((spec.seed, 4), (Hs, Hkv, D), spec.value_scale)
-    v_hist = _normal_bf16((spec.seed, 5), (Hs, Hkv, D), spec.value_scale)
+    q = _normal_bf16((spec.seed, 1), (T, Hq, D), spec.value_scale, dtype=spec.dtype)
+    k_new = _normal_bf16((spec.seed, 2), (T, Hkv, D), spec.value_scale, dtype=spec.dtype)
+    v_new = _normal_bf16((spec.seed, 3), (T, Hkv, D), spec.value_scale, dtype=spec.dtype)
+    k_hist = _normal_bf16((spec.seed, 4), (Hs, Hkv, D), spec.value_scale, dtype=spec.dtype)
+    v_hist = _normal_bf16((spec.seed, 5), (Hs, Hkv, D), spec.value_scale, dtype=spec.dtype)
     return Batch(spec, q_start, hist_start, table, max_blocks, num_blocks, q, k_new, v_new, k_hist, v_hist)
 
 
