@@ -84,12 +84,9 @@ def bench_migrate(args):
             tc.tc_kv_export(plan_a, pool, -1, src_k, src_v, buf, stream=stream)
             tc.tc_kv_import(plan_b, pool, -1, dst_k, dst_v, buf, stream=stream)
         ev = [[torch.cuda.Event(enable_timing=True) for _ in range(3)] for _ in range(args.steps)]
-        scratch = torch.empty(1 << 30, dtype=torch.uint8, device="cuda:0") if args.cold else None
         torch.cuda.synchronize()
         t0 = time.perf_counter()
         for i in range(args.steps):
-            if scratch is not None:
-                scratch.fill_(i & 0xFF)
             ev[i][0].record(stream)
             tc.tc_kv_export(plan_a, pool, -1, src_k, src_v, buf, stream=stream)
             ev[i][1].record(stream)
@@ -168,9 +165,11 @@ def main():
     ap.add_argument("--dtype", default="bf16", choices=["bf16", "fp16"],
                     help="element type of the tensors (bf16 is the headline; fp16 is the precision the paper ran in)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--graph", action="store_true",
+                    help="also time the step captured in a HIP graph and replayed (reported as graph_ms_per_step)")
     ap.add_argument("--cold", action="store_true",
-                    help="overwrite a 1 GiB scratch buffer before every step so that nothing of the batch is left in "
-                         "the 256 MiB memory-side cache; the step time is then the sum of the two event intervals")
+                    help="rotate the steps over several copies of the batch (separate pools, together over 1 GiB) so "
+                         "that no step finds its K/V in the 256 MiB memory-side cache, as with one layer after another")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="run a plain 1 GiB device copy three times and exit (counter calibration under rocprofv3 --pmc)")
     args = ap.parse_args()
@@ -219,22 +218,41 @@ def main():
         for _ in range(args.warmup):
             db.step()
         ev = [[torch.cuda.Event(enable_timing=True) for _ in range(3)] for _ in range(args.steps)]
+        copies = [db]
+        if args.cold:
+            n_copies = int(min(8, max(2, -(-(1 << 30) // max(work["bytes"], 1)))))
+            copies += [DeviceBatch(batch, stream=stream) for _ in range(n_copies - 1)]
+            for c in copies[1:]:
+                c.step()
         torch.cuda.synchronize()
         t0 = time.perf_counter()
         for i in range(args.steps):
+            cur = copies[i % len(copies)]
             ev[i][0].record(stream)
-            db.append()
+            cur.append()
             ev[i][1].record(stream)
-            db.attention()
+            cur.attention()
             ev[i][2].record(stream)
         torch.cuda.synchronize()
         wall = time.perf_counter() - t0
+        graph_ms = None
+        if args.graph:  # the same step captured once in a HIP graph and replayed: no per-launch host work
+            g = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(g, stream=stream):
+                db.append()
+                db.attention()
+            for _ in range(args.warmup):
+                g.replay()
+            torch.cuda.synchronize()
+            t1 = time.perf_counter()
+            for _ in range(args.steps):
+                g.replay()
+            torch.cuda.synchronize()
+            graph_ms = (time.perf_counter() - t1) / args.steps * 1e3
     attn_all = [e[1].elapsed_time(e[2]) for e in ev]
     append_ms = float(np.mean([e[0].elapsed_time(e[1]) for e in ev]))
     attn_ms = float(np.mean(attn_all))
     ms_per_step = wall / args.steps * 1e3
-    if args.cold:  # the wall clock includes the scratch fills; use the event intervals of the path itself
-        ms_per_step = float(np.mean([e[0].elapsed_time(e[2]) for e in ev]))
     T = work["tokens"]
 
     prefill_bound = work["flops"] / (PEAK_BF16_TFLOPS * 1e12) >= work["bytes"] / (PEAK_HBM_GBS * 1e9)
@@ -263,7 +281,7 @@ def main():
                        "head_dim": spec.head_dim, "block_size": spec.block_size, "num_seqs": spec.num_seqs,
                        "tokens": T, "prefill_chunk": int(spec.q_len.max()) if (spec.q_len > 1).any() else 0,
                        "sum_kv_len": work["sum_kv_len"], "seed": spec.seed, "cold_cache": bool(args.cold)},
-            "append_ms": append_ms, "attention_ms": attn_ms, "plan_ms": plan_ms,
+            "append_ms": append_ms, "attention_ms": attn_ms, "plan_ms": plan_ms, "graph_ms_per_step": graph_ms,
             "hbm_frac_of_step": work["bytes"] / (ms_per_step * 1e-3) / 1e9 / PEAK_HBM_GBS,
             "mfma_frac_of_step": work["flops"] / (ms_per_step * 1e-3) / 1e12 / PEAK_BF16_TFLOPS,
             "roofline": roofline}

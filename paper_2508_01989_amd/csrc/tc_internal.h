@@ -13,8 +13,12 @@ namespace tc {
 constexpr int kBlock = 16;          // tokens per KV page
 constexpr int kWgThreads = 256;     // threads per workgroup of the fused attention kernel
 constexpr int kWgWaves = kWgThreads / 64;
-constexpr int kWgPerCu = 2;         // workgroups of the fused kernel resident per compute unit
-constexpr int kPrefillRows = 32 * kWgWaves;  // (position, head) rows per prefill workgroup: 32 per wave
+#ifndef TC_ROW_BLOCKS
+#define TC_ROW_BLOCKS 1
+#endif
+constexpr int kWaveRowBlocks = TC_ROW_BLOCKS;  // 32-row blocks of a prefill workgroup each wave owns (1 or 2)
+constexpr int kWgPerCu = kWaveRowBlocks == 1 ? 2 : 1;  // workgroups of the fused kernel resident per compute unit
+constexpr int kPrefillRows = 32 * kWaveRowBlocks * kWgWaves;  // (position, head) rows per prefill workgroup
 constexpr int kItemInts = 8;        // int32 fields per work item
 constexpr int kAppendInts = 4;      // int32 fields per append segment: first packed row, tokens, first token index, pool block
 constexpr int kMaxSplitPages = 64;  // a decode split's page ids fit one wavefront register

@@ -22,9 +22,6 @@
 
 #include "tc_internal.h"
 
-#ifndef TC_ROWSUM_MFMA
-#define TC_ROWSUM_MFMA 0
-#endif
 
 namespace tc {
 
@@ -238,7 +235,6 @@ __global__ void __launch_bounds__(256) kv_migrate_kernel(const MigratePools pool
 //   S^T[token][row]  = sum_d K[token][d] Q[row][d]        (A = K from LDS, B = Q in registers)
 //   O^T[d][row]     += sum_token V^T[d][token] P^T[token][row]   (A = V^T from LDS, B = P)
 // with the online softmax (running max m, running sum l) kept per row in fp32.
-constexpr bool kRowSumOnMfma = TC_ROWSUM_MFMA;
 
 template <int D>
 struct PrefillCfg {
@@ -338,8 +334,9 @@ __device__ void prefill_item(const AttnArgs &A, const int32_t *__restrict__ it, 
     using x8 = typename E::x8;
     using x4 = typename E::x4;
     using el = typename E::t;
-    constexpr int KS = D / 16;  // k-steps of the QK^T product
-    constexpr int MT = D / 32;  // 32-row tiles of O^T
+    constexpr int KS = D / 16;      // k-steps of the QK^T product
+    constexpr int MT = D / 32;      // 32-row tiles of O^T
+    constexpr int RB = kWaveRowBlocks;  // 32-row blocks per wave: every K / V fragment read from LDS feeds RB MFMAs
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int n = lane & 31, hh = lane >> 5;
@@ -348,14 +345,21 @@ __device__ void prefill_item(const AttnArgs &A, const int32_t *__restrict__ it, 
     const int32_t *pages = A.pages + it[PF_PAGEOFF];
     const int G = A.G;
     const int n_rows = npos * G;
-    const int R = wave * 32 + n;
-    const bool row_valid = R < n_rows;
-    const int Rc = row_valid ? R : n_rows - 1;
-    const int pl = pos0 + Rc / G;
-    const int p_abs = ctx + pl;  // this lane's row attends over tokens 0..p_abs
-    const int64_t row_off = ((int64_t)(qrow0 + pl) * A.Hq + kvh * G + Rc % G) * D;
+    // Row block rb of this wave holds workgroup rows wave*32*RB + rb*32 .. +31; this lane's row of it:
+    bool row_valid[RB];
+    int Rc[RB], p_abs[RB];  // clamped row; absolute position: the row attends over tokens 0..p_abs
+    int64_t row_off[RB];
+#pragma unroll
+    for (int rb = 0; rb < RB; rb++) {
+        const int R = (wave * RB + rb) * 32 + n;
+        row_valid[rb] = R < n_rows;
+        Rc[rb] = row_valid[rb] ? R : n_rows - 1;
+        const int pl = pos0 + Rc[rb] / G;
+        p_abs[rb] = ctx + pl;
+        row_off[rb] = ((int64_t)(qrow0 + pl) * A.Hq + kvh * G + Rc[rb] % G) * D;
+    }
     // wave-uniform bounds of the rows this wave owns
-    const int r_lo = min(wave * 32, n_rows - 1), r_hi = min(wave * 32 + 31, n_rows - 1);
+    const int r_lo = min(wave * 32 * RB, n_rows - 1), r_hi = min(wave * 32 * RB + 32 * RB - 1, n_rows - 1);
     const int wave_pmin = ctx + pos0 + r_lo / G, wave_pmax = ctx + pos0 + r_hi / G;
     const int kv_len = ctx + pos0 + npos;  // tokens this workgroup may read (all appended already)
     // KV tiles [t_begin, t_end) of the item; p_slot < 0: the whole range, results go to `out`
@@ -363,25 +367,23 @@ __device__ void prefill_item(const AttnArgs &A, const int32_t *__restrict__ it, 
     const float c_log2 = A.scale_log2;
     const int v_lane_off = n * 32 + ((hh ^ ((n >> 3) & 1)) * 16);  // this lane's 16 bytes inside a 32-row V^T tile
 
-    x8 qreg[KS];
+    x8 qreg[RB][KS];
 #pragma unroll
-    for (int kk = 0; kk < KS; kk++) qreg[kk] = *reinterpret_cast<const x8 *>(A.q + row_off + (2 * kk + hh) * 8);
+    for (int rb = 0; rb < RB; rb++)
+#pragma unroll
+        for (int kk = 0; kk < KS; kk++) qreg[rb][kk] = *reinterpret_cast<const x8 *>(A.q + row_off[rb] + (2 * kk + hh) * 8);
 
-    f32x16 o[MT];
+    f32x16 o[RB][MT];
+    float m_run[RB], l_run[RB];  // running row maximum (log2 domain) and row sum (this half-wave's share)
 #pragma unroll
-    for (int c = 0; c < MT; c++)
+    for (int rb = 0; rb < RB; rb++) {
+        m_run[rb] = -1e30f;
+        l_run[rb] = 0.f;
 #pragma unroll
-        for (int r = 0; r < 16; r++) o[c][r] = 0.f;
-    float m_run = -1e30f;  // running row maximum, log2 domain
-    // Running row sum.  kRowSumOnMfma: accumulate it on the matrix cores as ones^T P^T (every
-    // element of lsum holds the sum over both half-waves); otherwise add on the vector ALU.
-    f32x16 lsum;
+        for (int c = 0; c < MT; c++)
 #pragma unroll
-    for (int r = 0; r < 16; r++) lsum[r] = 0.f;
-    float l_run = 0.f;
-    x8 ones;
-#pragma unroll
-    for (int e = 0; e < 8; e++) ones[e] = (el)1.0f;
+            for (int r = 0; r < 16; r++) o[rb][c][r] = 0.f;
+    }
 
     int page_id = prefill_page_id<D>(pages, n_pages, t_begin, wave);
     prefill_fetch<D>(A, kvh, page_id, lds, lds + 2 * C::kTileBytes, wave, lane);
@@ -402,68 +404,73 @@ __device__ void prefill_item(const AttnArgs &A, const int32_t *__restrict__ it, 
 
         const int tok0 = tile * C::kTileTokens;
         if (tok0 <= wave_pmax) {  // otherwise every (row, token) pair of this wave is masked
-            f32x16 s[2];
+            f32x16 s[RB][2];
 #pragma unroll
             for (int mt = 0; mt < 2; mt++) {
 #pragma unroll
-                for (int r = 0; r < 16; r++) s[mt][r] = 0.f;
+                for (int rb = 0; rb < RB; rb++)
+#pragma unroll
+                    for (int r = 0; r < 16; r++) s[rb][mt][r] = 0.f;
                 const char *kp = ks + (2 * mt + (n >> 4)) * C::kPageBytes + (n & 15) * 16;
 #pragma unroll
                 for (int kk = 0; kk < KS; kk++) {
                     const x8 a = *reinterpret_cast<const x8 *>(kp + (2 * kk + hh) * (kBlock * 16));
-                    s[mt] = E::mfma32(a, qreg[kk], s[mt]);
+#pragma unroll
+                    for (int rb = 0; rb < RB; rb++) s[rb][mt] = E::mfma32(a, qreg[rb][kk], s[rb][mt]);
                 }
             }
             if (tok0 + C::kTileTokens - 1 > wave_pmin) {  // the diagonal crosses this tile: causal mask
 #pragma unroll
+                for (int rb = 0; rb < RB; rb++)
+#pragma unroll
+                    for (int mt = 0; mt < 2; mt++)
+#pragma unroll
+                        for (int r = 0; r < 16; r++) {
+                            const int j = tok0 + 32 * mt + 8 * (r >> 2) + 4 * hh + (r & 3);
+                            s[rb][mt][r] = (j <= p_abs[rb]) ? s[rb][mt][r] : -INFINITY;
+                        }
+            }
+#pragma unroll
+            for (int rb = 0; rb < RB; rb++) {
+                float mx = s[rb][0][0];
+#pragma unroll
+                for (int mt = 0; mt < 2; mt++)
+#pragma unroll
+                    for (int r = 0; r < 16; r++) mx = fmaxf(mx, s[rb][mt][r]);
+                mx = half_swap_max(mx);
+                const float m_new = fmaxf(m_run[rb], mx * c_log2);
+                if (__builtin_amdgcn_ballot_w64(m_new > m_run[rb]) != 0) {  // some row's maximum moved: rescale
+                    const float alpha = fast_exp2(m_run[rb] - m_new);
+                    m_run[rb] = m_new;
+                    l_run[rb] *= alpha;
+#pragma unroll
+                    for (int c = 0; c < MT; c++)
+#pragma unroll
+                        for (int r = 0; r < 16; r++) o[rb][c][r] *= alpha;
+                }
+                float psum = 0.f;
+#pragma unroll
                 for (int mt = 0; mt < 2; mt++)
 #pragma unroll
                     for (int r = 0; r < 16; r++) {
-                        const int j = tok0 + 32 * mt + 8 * (r >> 2) + 4 * hh + (r & 3);
-                        s[mt][r] = (j <= p_abs) ? s[mt][r] : -INFINITY;
+                        const float pv = fast_exp2(__builtin_fmaf(s[rb][mt][r], c_log2, -m_run[rb]));
+                        s[rb][mt][r] = pv;
+                        psum += pv;
                     }
+                l_run[rb] += psum;
             }
-            float mx = s[0][0];
-#pragma unroll
-            for (int mt = 0; mt < 2; mt++)
-#pragma unroll
-                for (int r = 0; r < 16; r++) mx = fmaxf(mx, s[mt][r]);
-            mx = half_swap_max(mx);
-            const float m_new = fmaxf(m_run, mx * c_log2);
-            if (__builtin_amdgcn_ballot_w64(m_new > m_run) != 0) {  // some row's maximum moved: rescale
-                const float alpha = fast_exp2(m_run - m_new);
-                m_run = m_new;
-                if (kRowSumOnMfma) {
-#pragma unroll
-                    for (int r = 0; r < 16; r++) lsum[r] *= alpha;
-                } else {
-                    l_run *= alpha;
-                }
-#pragma unroll
-                for (int c = 0; c < MT; c++)
-#pragma unroll
-                    for (int r = 0; r < 16; r++) o[c][r] *= alpha;
-            }
-            float psum = 0.f;
-#pragma unroll
-            for (int mt = 0; mt < 2; mt++)
-#pragma unroll
-                for (int r = 0; r < 16; r++) {
-                    const float pv = fast_exp2(__builtin_fmaf(s[mt][r], c_log2, -m_run));
-                    s[mt][r] = pv;
-                    if (!kRowSumOnMfma) psum += pv;
-                }
-            if (!kRowSumOnMfma) l_run += psum;
 #pragma unroll
             for (int b = 0; b < C::kTilePages; b++) {
-                x8 pb;
+                x8 pb[RB];
 #pragma unroll
-                for (int e = 0; e < 8; e++) pb[e] = (el)s[b >> 1][8 * (b & 1) + e];
-                if (kRowSumOnMfma) lsum = E::mfma32(ones, pb, lsum);
+                for (int rb = 0; rb < RB; rb++)
+#pragma unroll
+                    for (int e = 0; e < 8; e++) pb[rb][e] = (el)s[rb][b >> 1][8 * (b & 1) + e];
 #pragma unroll
                 for (int c = 0; c < MT; c++) {
                     const x8 a = *reinterpret_cast<const x8 *>(vs + b * C::kPageBytes + c * (32 * 32) + v_lane_off);
-                    o[c] = E::mfma32(a, pb, o[c]);
+#pragma unroll
+                    for (int rb = 0; rb < RB; rb++) o[rb][c] = E::mfma32(a, pb[rb], o[rb][c]);
                 }
             }
         }
@@ -473,38 +480,38 @@ __device__ void prefill_item(const AttnArgs &A, const int32_t *__restrict__ it, 
         __syncthreads();
     }
 
-    l_run = kRowSumOnMfma ? lsum[0] : half_swap_sum(l_run);
-    if (p_slot >= 0) {
-        // A piece of a cut item: unnormalised accumulators, running maximum (log2 domain) and row sum
-        // go to the workspace, in the partial layout the decode splits use; rows that see no key of
-        // this piece carry (m, l, o) = (-1e30, 0, 0) and get weight 0 in the merge.
-        if (row_valid) {
-            const int64_t prow = ((int64_t)(p_slot + (Rc / G) * p_k)) * G + Rc % G;
+#pragma unroll
+    for (int rb = 0; rb < RB; rb++) {
+        const float l = half_swap_sum(l_run[rb]);
+        if (!row_valid[rb]) continue;
+        if (p_slot >= 0) {
+            // A piece of a cut item: unnormalised accumulators, running maximum (log2 domain) and row sum
+            // go to the workspace, in the partial layout the decode splits use; rows that see no key of
+            // this piece carry (m, l, o) = (-1e30, 0, 0) and get weight 0 in the merge.
+            const int64_t prow = ((int64_t)(p_slot + (Rc[rb] / G) * p_k)) * G + Rc[rb] % G;
             float *dst = A.ws_o + prow * D + 4 * hh;
 #pragma unroll
             for (int c = 0; c < MT; c++)
 #pragma unroll
                 for (int q4 = 0; q4 < 4; q4++)
                     *reinterpret_cast<f32x4 *>(dst + 32 * c + 8 * q4) =
-                        f32x4{o[c][4 * q4], o[c][4 * q4 + 1], o[c][4 * q4 + 2], o[c][4 * q4 + 3]};
+                        f32x4{o[rb][c][4 * q4], o[rb][c][4 * q4 + 1], o[rb][c][4 * q4 + 2], o[rb][c][4 * q4 + 3]};
             if (hh == 0) {
-                A.ws_ml[prow * 2] = m_run;
-                A.ws_ml[prow * 2 + 1] = l_run;
+                A.ws_ml[prow * 2] = m_run[rb];
+                A.ws_ml[prow * 2 + 1] = l;
             }
+        } else {
+            const float inv = 1.f / l;
+#pragma unroll
+            for (int c = 0; c < MT; c++)
+#pragma unroll
+                for (int q4 = 0; q4 < 4; q4++) {
+                    x4 w;
+#pragma unroll
+                    for (int e = 0; e < 4; e++) w[e] = (el)(o[rb][c][4 * q4 + e] * inv);
+                    *reinterpret_cast<x4 *>(A.out + row_off[rb] + 32 * c + 8 * q4 + 4 * hh) = w;
+                }
         }
-        return;
-    }
-    const float inv = 1.f / l_run;
-    if (row_valid) {
-#pragma unroll
-        for (int c = 0; c < MT; c++)
-#pragma unroll
-            for (int q4 = 0; q4 < 4; q4++) {
-                x4 w;
-#pragma unroll
-                for (int e = 0; e < 4; e++) w[e] = (el)(o[c][4 * q4 + e] * inv);
-                *reinterpret_cast<x4 *>(A.out + row_off + 32 * c + 8 * q4 + 4 * hh) = w;
-            }
     }
 }
 
