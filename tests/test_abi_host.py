@@ -220,3 +220,20 @@ def test_small_prefill_batches_are_cut_into_kv_pieces(tc, name, Hq, Hkv, q_len, 
     info = check_work_list(tc, sp, table, nb)
     assert (info.num_prefill_pieces > info.num_prefill_items) == cut
     assert info.num_prefill_pieces <= 8 * info.num_prefill_items
+
+
+@pytest.mark.parametrize("seed", range(25))
+def test_work_list_invariants_on_random_batches(tc, seed):
+    """Random mixes of prefill chunks and decodes, random head shapes: the same coverage checks."""
+    rng = np.random.default_rng(4000 + seed)
+    Hkv = int(rng.choice([1, 2, 4, 8]))
+    G = int(rng.choice([1, 2, 3, 4, 5, 8, 16]))
+    n_pf, n_dec = int(rng.integers(0, 4)), int(rng.integers(0, 40))
+    if n_pf + n_dec == 0:
+        n_dec = 1
+    q_len = [int(rng.integers(2, 700)) for _ in range(n_pf)] + [1] * n_dec
+    ctx = [int(rng.integers(0, 6000)) for _ in range(n_pf)] + [int(rng.integers(0, 9000)) for _ in range(n_dec)]
+    order = rng.permutation(len(q_len))
+    sp = W.custom_spec(f"rand{seed}", Hkv * G, Hkv, int(rng.choice([64, 128])), [q_len[i] for i in order], [ctx[i] for i in order])
+    table, mb, nb = W.make_tables(sp, rng)
+    check_work_list(tc, sp, table, nb)

@@ -59,6 +59,7 @@ SMALL = {
     "decode_page_boundaries": (8, 2, 128, [1, 1, 1, 1, 1], [14, 15, 16, 31, 32]),
     "decode_split_boundaries": (8, 2, 128, [1, 1, 1, 1], [126, 127, 128, 255]),
     "decode_long_ragged": (32, 8, 128, [1, 1, 1], [3000, 1025, 777]),
+    "decode_more_than_64_splits": (8, 2, 128, [1, 1], [20000, 8191]),  # 157 and 64 splits of 128: two merge passes
     "prefill_two_rows": (4, 1, 128, [2], [0]),
     "prefill_ragged_tiles": (8, 2, 128, [77], [0]),
     "prefill_offset_not_page_aligned": (8, 2, 128, [130], [37]),
