@@ -17,7 +17,9 @@ constexpr int kWgWaves = kWgThreads / 64;
 #define TC_ROW_BLOCKS 1
 #endif
 constexpr int kWaveRowBlocks = TC_ROW_BLOCKS;  // 32-row blocks of a prefill workgroup each wave owns (1 or 2)
-constexpr int kWgPerCu = kWaveRowBlocks == 1 ? 2 : 1;  // workgroups of the fused kernel resident per compute unit
+// Workgroups of the fused kernel resident per compute unit: with 32 rows per wave the kernel needs 168
+// VGPRs and 48 KiB of LDS, so three fit; the 64-row variant takes a whole SIMD's registers per wave.
+constexpr int kWgPerCu = kWaveRowBlocks == 1 ? 3 : 1;
 constexpr int kPrefillRows = 32 * kWaveRowBlocks * kWgWaves;  // (position, head) rows per prefill workgroup
 constexpr int kItemInts = 8;        // int32 fields per work item
 constexpr int kAppendInts = 4;      // int32 fields per append segment: first packed row, tokens, first token index, pool block

@@ -38,6 +38,11 @@ struct Bf16 {
     typedef __bf16 x2 __attribute__((ext_vector_type(2)));
     static __device__ __forceinline__ f32x16_t mfma32(x8 a, x8 b, f32x16_t c) { return __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c, 0, 0, 0); }
     static __device__ __forceinline__ f32x4_t mfma16(x8 a, x8 b, f32x4_t c) { return __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, b, c, 0, 0, 0); }
+    // 16x16x16: contraction over the 16 tokens of one page
+    static __device__ __forceinline__ f32x4_t mfma16k16(x4 a, x4 b, f32x4_t c) {
+        typedef short s4 __attribute__((ext_vector_type(4)));
+        return __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(__builtin_bit_cast(s4, a), __builtin_bit_cast(s4, b), c, 0, 0, 0);
+    }
 };
 struct Fp16 {
     typedef _Float16 t;
@@ -46,6 +51,7 @@ struct Fp16 {
     typedef _Float16 x2 __attribute__((ext_vector_type(2)));
     static __device__ __forceinline__ f32x16_t mfma32(x8 a, x8 b, f32x16_t c) { return __builtin_amdgcn_mfma_f32_32x32x16_f16(a, b, c, 0, 0, 0); }
     static __device__ __forceinline__ f32x4_t mfma16(x8 a, x8 b, f32x4_t c) { return __builtin_amdgcn_mfma_f32_16x16x32_f16(a, b, c, 0, 0, 0); }
+    static __device__ __forceinline__ f32x4_t mfma16k16(x4 a, x4 b, f32x4_t c) { return __builtin_amdgcn_mfma_f32_16x16x16f16(a, b, c, 0, 0, 0); }
 };
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
@@ -243,7 +249,10 @@ struct PrefillCfg {
     static constexpr int kPageBytes = kBlock * D * 2;               // one (page, KV head) tile of K or of V
     static constexpr int kTileBytes = kTilePages * kPageBytes;      // K part or V part of one LDS stage
     static constexpr int kRuns = kPageBytes / 1024;                 // 1 KiB wave-wide loads per page and tensor
-    static constexpr int kLdsBytes = 2 * 2 * kTileBytes;            // two stages of K and V
+    // Two LDS stages of K (tile t+1 is copied while tile t is used) and one of V: the V tile of an
+    // iteration is copied at its top and awaited, with a barrier of its own, between the softmax and the
+    // second product.  48 KiB at D = 128, so that three workgroups fit the 160 KiB of a compute unit.
+    static constexpr int kLdsBytes = 3 * kTileBytes;
 };
 
 // N direct-to-LDS loads of 1 KiB each (16 bytes per lane) at immediate offsets 0, 1024, ...
@@ -286,8 +295,8 @@ __device__ __forceinline__ void prefill_fetch(const AttnArgs &A, int kvh, int pa
     const gptr_t vsrc = (gptr_t)(A.v_pool + base + d * kBlock + half * 8);
     const lptr_t kdst = (lptr_t)(lds_k + wave * C::kPageBytes);
     const lptr_t vdst = (lptr_t)(lds_v + wave * C::kPageBytes);
-    lds_load_runs<C::kRuns>(ksrc, kdst);
-    lds_load_runs<C::kRuns>(vsrc, vdst);
+    if (lds_k) lds_load_runs<C::kRuns>(ksrc, kdst);
+    if (lds_v) lds_load_runs<C::kRuns>(vsrc, vdst);
 }
 
 // After this thread's own direct-to-LDS loads of `tile` have landed: slots at or past `kv_len`
@@ -385,26 +394,32 @@ __device__ void prefill_item(const AttnArgs &A, const int32_t *__restrict__ it, 
             for (int r = 0; r < 16; r++) o[rb][c][r] = 0.f;
     }
 
+    char *const v_lds = lds + 2 * C::kTileBytes;
     int page_id = prefill_page_id<D>(pages, n_pages, t_begin, wave);
-    prefill_fetch<D>(A, kvh, page_id, lds, lds + 2 * C::kTileBytes, wave, lane);
+    int page_v = page_id;  // page whose V this wave copies at the top of the next iteration
+    prefill_fetch<D>(A, kvh, page_id, lds, nullptr, wave, lane);
     page_id = prefill_page_id<D>(pages, n_pages, t_begin + 1, wave);
     wait_all_loads();
-    if ((t_begin + 1) * C::kTileTokens > kv_len) prefill_fix_tail<D>(lds + 2 * C::kTileBytes, t_begin, wave, lane, kv_len);
     __syncthreads();
 
     for (int tile = t_begin; tile < t_end; tile++) {
         const int cur = (tile - t_begin) & 1;
         const char *ks = lds + cur * C::kTileBytes;
-        const char *vs = lds + 2 * C::kTileBytes + cur * C::kTileBytes;
+        const char *vs = v_lds;
         const bool more = tile + 1 < t_end;
-        if (more) {  // stage cur^1 was last read before the barrier that ended the previous iteration
-            prefill_fetch<D>(A, kvh, page_id, lds + (cur ^ 1) * C::kTileBytes, lds + 2 * C::kTileBytes + (cur ^ 1) * C::kTileBytes, wave, lane);
+        // The V buffer and K stage cur^1 were last read before the barrier that ended the previous
+        // iteration: copy this tile's V (needed after the softmax) and the next tile's K.
+        prefill_fetch<D>(A, kvh, page_v, nullptr, v_lds, wave, lane);
+        page_v = page_id;
+        if (more) {
+            prefill_fetch<D>(A, kvh, page_id, lds + (cur ^ 1) * C::kTileBytes, nullptr, wave, lane);
             page_id = prefill_page_id<D>(pages, n_pages, tile + 2, wave);
         }
 
         const int tok0 = tile * C::kTileTokens;
-        if (tok0 <= wave_pmax) {  // otherwise every (row, token) pair of this wave is masked
-            f32x16 s[RB][2];
+        const bool active = tok0 <= wave_pmax;  // otherwise every (row, token) pair of this wave is masked
+        f32x16 s[RB][2];
+        if (active) {
 #pragma unroll
             for (int mt = 0; mt < 2; mt++) {
 #pragma unroll
@@ -459,6 +474,14 @@ __device__ void prefill_item(const AttnArgs &A, const int32_t *__restrict__ it, 
                     }
                 l_run[rb] += psum;
             }
+        }
+        // This iteration's V tile: this wave's own copy has landed (the K loads issued after it may still
+        // be in flight); patch the tail, then every wave's part is visible after the barrier.
+        if (more) asm volatile("s_waitcnt vmcnt(%0)" ::"n"(C::kRuns) : "memory");
+        else wait_all_loads();
+        if ((tile + 1) * C::kTileTokens > kv_len) prefill_fix_tail<D>(v_lds, tile, wave, lane, kv_len);
+        __syncthreads();
+        if (active) {
 #pragma unroll
             for (int b = 0; b < C::kTilePages; b++) {
                 x8 pb[RB];
@@ -474,9 +497,7 @@ __device__ void prefill_item(const AttnArgs &A, const int32_t *__restrict__ it, 
                 }
             }
         }
-        wait_all_loads();
-        if (more && (tile + 2) * C::kTileTokens > kv_len)
-            prefill_fix_tail<D>(lds + 2 * C::kTileBytes + (cur ^ 1) * C::kTileBytes, tile + 1, wave, lane, kv_len);
+        wait_all_loads();  // the next tile's K
         __syncthreads();
     }
 
@@ -521,88 +542,76 @@ __device__ void prefill_item(const AttnArgs &A, const int32_t *__restrict__ it, 
 // ------------------------------------------------------------------------------------
 // Lane l: head column j = l % 16, token group g = l / 16.  Per page:
 //   S^T[token][head] = sum_d K[token][d] Q[head][d]   16x16x32, D/32 steps; lane gets tokens 4g..4g+3
-//   O^T[d][head]    += sum_token V^T[d][token] P^T[token][head]   contraction over the 32 tokens
-//                      of a page pair: lane feeds tokens 4g..4g+3 of either page
+//   O^T[d][head]    += sum_token V^T[d][token] P^T[token][head]   16x16x16, contraction over the page's
+//                      16 tokens: lane feeds tokens 4g..4g+3
+// Pages resident in registers per wave: one being consumed, the rest in flight.  Two keep the whole
+// kernel within 168 VGPRs (three waves per SIMD); three or four measured the same bandwidth.
+constexpr int kDecodeStages = 2;
+
 template <int D>
-struct DecodeStage {  // K and V of one page pair, in MFMA A-operand registers
-    u32x4 k[2][D / 32];
-    u32x2 v[2][D / 16];
+struct DecodePage {  // K and V of one page, in MFMA A-operand registers
+    u32x4 k[D / 32];
+    u32x2 v[D / 16];
 };
 
 // KV pages are read exactly once per launch, by one wavefront: stream them past the caches.
 template <int D>
-__device__ __forceinline__ void decode_fetch(const AttnArgs &A, int kvh, int id0, int id1, int j, int g,
-                                             DecodeStage<D> &st) {
+__device__ __forceinline__ void decode_fetch(const AttnArgs &A, int kvh, int id, int j, int g, DecodePage<D> &st) {
     const int64_t tile_elems = (int64_t)kBlock * D;
-    const int ids[2] = {id0, id1};
+    const uint16_t *kb = A.k_pool + ((int64_t)id * A.Hkv + kvh) * tile_elems;
+    const uint16_t *vb = A.v_pool + ((int64_t)id * A.Hkv + kvh) * tile_elems;
 #pragma unroll
-    for (int b = 0; b < 2; b++) {
-        const uint16_t *kb = A.k_pool + ((int64_t)ids[b] * A.Hkv + kvh) * tile_elems;
-        const uint16_t *vb = A.v_pool + ((int64_t)ids[b] * A.Hkv + kvh) * tile_elems;
+    for (int kk = 0; kk < D / 32; kk++)
+        st.k[kk] = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(kb + ((4 * kk + g) * kBlock + j) * 8));
 #pragma unroll
-        for (int kk = 0; kk < D / 32; kk++)
-            st.k[b][kk] = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(kb + ((4 * kk + g) * kBlock + j) * 8));
-#pragma unroll
-        for (int c = 0; c < D / 16; c++)
-            st.v[b][c] = __builtin_nontemporal_load(reinterpret_cast<const u32x2 *>(vb + (16 * c + j) * kBlock + v_slot(4 * g)));
-    }
+    for (int c = 0; c < D / 16; c++)
+        st.v[c] = __builtin_nontemporal_load(reinterpret_cast<const u32x2 *>(vb + (16 * c + j) * kBlock + v_slot(4 * g)));
 }
 
+// One page: S^T = K Q^T (16 tokens x 16 head columns, contraction over D), online softmax over the
+// 16 tokens, O^T += V^T P^T (contraction over the page's 16 tokens).
 template <int D, class E>
-__device__ __forceinline__ void decode_consume(const AttnArgs &A, DecodeStage<D> &st, const typename E::x8 (&qreg)[D / 32],
-                                               int n_valid0, int n_valid1, int g, f32x4 (&o)[D / 16], float &m_run,
-                                               float &l_run) {
+__device__ __forceinline__ void decode_consume(const AttnArgs &A, DecodePage<D> &st, const typename E::x8 (&qreg)[D / 32],
+                                               int n_valid, int g, f32x4 (&o)[D / 16], float &m_run, float &l_run) {
     using x8 = typename E::x8;
+    using x4 = typename E::x4;
     using el = typename E::t;
     constexpr int KS = D / 32, MT = D / 16;
-    const int n_valid[2] = {n_valid0, n_valid1};
-    f32x4 s[2];
+    f32x4 s = f32x4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-    for (int b = 0; b < 2; b++) {
-        s[b] = f32x4{0.f, 0.f, 0.f, 0.f};
+    for (int kk = 0; kk < KS; kk++) s = E::mfma16(__builtin_bit_cast(x8, st.k[kk]), qreg[kk], s);
+    if (n_valid < kBlock) {  // the split ends inside this page: mask scores, make V finite
 #pragma unroll
-        for (int kk = 0; kk < KS; kk++)
-            s[b] = E::mfma16(__builtin_bit_cast(x8, st.k[b][kk]), qreg[kk], s[b]);
-    }
-    if (n_valid1 < kBlock) {  // the split ends inside this pair: mask scores, make V finite
+        for (int r = 0; r < 4; r++) s[r] = (4 * g + r < n_valid) ? s[r] : -INFINITY;
 #pragma unroll
-        for (int b = 0; b < 2; b++) {
-#pragma unroll
-            for (int r = 0; r < 4; r++) s[b][r] = (4 * g + r < n_valid[b]) ? s[b][r] : -INFINITY;
-#pragma unroll
-            for (int c = 0; c < MT; c++) {
-                u32x2 w = st.v[b][c];
-                if (4 * g + 0 >= n_valid[b]) w[0] &= 0xFFFF0000u;
-                if (4 * g + 1 >= n_valid[b]) w[0] &= 0x0000FFFFu;
-                if (4 * g + 2 >= n_valid[b]) w[1] &= 0xFFFF0000u;
-                if (4 * g + 3 >= n_valid[b]) w[1] &= 0x0000FFFFu;
-                st.v[b][c] = w;
-            }
+        for (int c = 0; c < MT; c++) {
+            u32x2 w = st.v[c];
+            if (4 * g + 0 >= n_valid) w[0] &= 0xFFFF0000u;
+            if (4 * g + 1 >= n_valid) w[0] &= 0x0000FFFFu;
+            if (4 * g + 2 >= n_valid) w[1] &= 0xFFFF0000u;
+            if (4 * g + 3 >= n_valid) w[1] &= 0x0000FFFFu;
+            st.v[c] = w;
         }
     }
-    float mx = fmaxf(fmaxf(fmaxf(s[0][0], s[0][1]), fmaxf(s[0][2], s[0][3])),
-                     fmaxf(fmaxf(s[1][0], s[1][1]), fmaxf(s[1][2], s[1][3])));
+    float mx = fmaxf(fmaxf(s[0], s[1]), fmaxf(s[2], s[3]));
     mx = fmaxf(mx, xor_lanes(mx, 16));
     mx = half_swap_max(mx);
     const float m_new = fmaxf(m_run, mx * A.scale_log2);
     const float alpha = fast_exp2(m_run - m_new);
     m_run = m_new;
-    x8 pb;
+    x4 pb;
     float psum = 0.f;
 #pragma unroll
-    for (int b = 0; b < 2; b++)
-#pragma unroll
-        for (int r = 0; r < 4; r++) {
-            const float pv = fast_exp2(__builtin_fmaf(s[b][r], A.scale_log2, -m_new));
-            psum += pv;
-            pb[4 * b + r] = (el)pv;
-        }
+    for (int r = 0; r < 4; r++) {
+        const float pv = fast_exp2(__builtin_fmaf(s[r], A.scale_log2, -m_new));
+        psum += pv;
+        pb[r] = (el)pv;
+    }
     l_run = l_run * alpha + psum;
 #pragma unroll
     for (int c = 0; c < MT; c++) {
         o[c] *= alpha;
-        const u32x4 aw = {st.v[0][c][0], st.v[0][c][1], st.v[1][c][0], st.v[1][c][1]};
-        o[c] = E::mfma16(__builtin_bit_cast(x8, aw), pb, o[c]);
+        o[c] = E::mfma16k16(__builtin_bit_cast(x4, st.v[c]), pb, o[c]);
     }
 }
 
@@ -613,6 +622,7 @@ __device__ void decode_item(const AttnArgs &A, const int32_t *__restrict__ it) {
     using el = typename E::t;
     constexpr int KS = D / 32;  // k-steps of K Q^T
     constexpr int MT = D / 16;  // 16-row tiles of O^T
+    constexpr int NS = kDecodeStages;
     const int lane = threadIdx.x & 63;
     const int j = lane & 15, g = lane >> 4;
     const int kvh = it[DC_KVH], t0 = it[DC_BEGIN], t1 = it[DC_END], qrow = it[DC_QROW], slot = it[DC_SLOT];
@@ -637,21 +647,21 @@ __device__ void decode_item(const AttnArgs &A, const int32_t *__restrict__ it) {
     for (int c = 0; c < MT; c++) o[c] = f32x4{0.f, 0.f, 0.f, 0.f};
     float m_run = -1e30f, l_run = 0.f;
 
-    // Page pairs, two register stages: the loads of pair i+1 are in flight while pair i is
-    // consumed.  A phantom second page (odd page count) re-reads the last page and is masked.
-    DecodeStage<D> sa, sb;
-    const int last = n_pg - 1;
-    decode_fetch<D>(A, kvh, __builtin_amdgcn_readlane(my_page, 0), __builtin_amdgcn_readlane(my_page, min(1, last)), j, g, sa);
-    for (int pp = 0; pp < n_pg; pp += 4) {
-        if (pp + 2 < n_pg)
-            decode_fetch<D>(A, kvh, __builtin_amdgcn_readlane(my_page, pp + 2),
-                            __builtin_amdgcn_readlane(my_page, min(pp + 3, last)), j, g, sb);
-        decode_consume<D, E>(A, sa, qreg, n_tok - pp * kBlock, n_tok - (pp + 1) * kBlock, g, o, m_run, l_run);
-        if (pp + 2 < n_pg) {
-            if (pp + 4 < n_pg)
-                decode_fetch<D>(A, kvh, __builtin_amdgcn_readlane(my_page, pp + 4),
-                                __builtin_amdgcn_readlane(my_page, min(pp + 5, last)), j, g, sa);
-            decode_consume<D, E>(A, sb, qreg, n_tok - (pp + 2) * kBlock, n_tok - (pp + 3) * kBlock, g, o, m_run, l_run);
+    // A ring of NS register stages, one page each: while page i is consumed the loads of pages
+    // i+1 .. i+NS-1 are in flight.
+    DecodePage<D> st[NS];
+#pragma unroll
+    for (int u = 0; u < NS - 1; u++)
+        if (u < n_pg) decode_fetch<D>(A, kvh, __builtin_amdgcn_readlane(my_page, u), j, g, st[u]);
+    for (int pp = 0; pp < n_pg; pp += NS) {
+#pragma unroll
+        for (int u = 0; u < NS; u++) {
+            const int cur = pp + u;
+            if (cur < n_pg) {
+                const int nxt = cur + NS - 1;
+                if (nxt < n_pg) decode_fetch<D>(A, kvh, __builtin_amdgcn_readlane(my_page, nxt), j, g, st[(u + NS - 1) % NS]);
+                decode_consume<D, E>(A, st[u], qreg, n_tok - cur * kBlock, g, o, m_run, l_run);
+            }
         }
     }
     l_run += xor_lanes(l_run, 16);
