@@ -31,7 +31,7 @@ tc_status check_pool_matches(const tc_plan *plan, const tc_kv_pool *pool, bool n
 // Decode KV ranges are cut into equal splits so that work items are uniform; the split
 // is the largest of 1024..128 tokens that still yields enough items to fill the chip.
 static int choose_split(int64_t decode_token_heads) {
-    const int64_t want_items = 4 * 256 * kWgWaves;  // a few wavefronts of work per wave slot
+    const int64_t want_items = (int64_t)kNumCu * kWgPerCu * kWgWaves;  // one item per resident wavefront (finer splits measured slower)
     for (int split = kMaxSplitPages * kBlock; split > 128; split /= 2)
         if (decode_token_heads / split >= want_items) return split;
     return 128;
