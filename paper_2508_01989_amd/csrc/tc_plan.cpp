@@ -201,21 +201,42 @@ tc_status build_plan(const tc_kv_pool *pool, const tc_batch *b, tc_plan **out) {
         int item = 0;
         for (const Tile &t : tiles) {
             const int n_tiles = (int)((t.cost - 1) / kPrefillTileTokens) + 1;
+            const int item0 = item, slot_base = next_slot;
             for (int h = 0; h < Hkv; h++, pf += kItemInts, item++) {
                 pf[PF_SEQ] = t.seq; pf[PF_KVH] = h; pf[PF_POS0] = t.pos0; pf[PF_NPOS] = t.npos;
                 pf[PF_QROW0] = p->q_start[t.seq]; pf[PF_CTX] = p->ctx_len[t.seq];
                 pf[PF_PAGEOFF] = p->page_off[t.seq]; pf[PF_NPAGES] = p->page_off[t.seq + 1] - p->page_off[t.seq];
-                if (t.k == 1) { pieces.push_back({item, 0, n_tiles, -1, 1}); continue; }
-                for (int c = 0; c < t.k; c++)
-                    pieces.push_back({item, (int)((int64_t)n_tiles * c / t.k), (int)((int64_t)n_tiles * (c + 1) / t.k), next_slot + c, t.k});
+                if (t.k == 1) continue;
                 for (int i = 0; i < t.npos; i++, mg += kItemInts) {
                     mg[MG_SEQ] = t.seq; mg[MG_KVH] = h; mg[MG_QROW] = p->q_start[t.seq] + t.pos0 + i;
                     mg[MG_SLOT0] = next_slot + i * t.k; mg[MG_NSPLIT] = t.k;
                 }
                 next_slot += t.k * t.npos;
             }
+            // pieces with the KV head as the fastest index, like the items
+            for (int c = 0; c < t.k; c++)
+                for (int h = 0; h < Hkv; h++) {
+                    if (t.k == 1) { pieces.push_back({item0 + h, 0, n_tiles, -1, 1}); continue; }
+                    pieces.push_back({item0 + h, (int)((int64_t)n_tiles * c / t.k), (int)((int64_t)n_tiles * (c + 1) / t.k),
+                                      slot_base + h * t.k * t.npos + c, t.k});
+                }
         }
         std::stable_sort(pieces.begin(), pieces.end(), [](const Piece &x, const Piece &y) { return x.t1 - x.t0 > y.t1 - y.t0; });
+        // The first kWgPerCu * kNumCu workgroups are resident together, workgroup i on compute unit
+        // i mod kNumCu (observed dispatch order).  Handing every second round of kNumCu pieces out in
+        // reverse puts the heaviest piece of one round beside the lightest of the next, so the compute
+        // units finish together instead of in order of their load.  Groups of Hkv consecutive pieces (one
+        // per KV head) are kept intact so that workgroup id mod Hkv still names the KV head.
+        {
+            const size_t grp = (kNumCu % Hkv == 0) ? (size_t)Hkv : 1;
+            for (int r = 1; r < kWgPerCu; r += 2) {
+                const size_t lo = (size_t)r * kNumCu, hi = std::min(pieces.size(), lo + kNumCu);
+                if (lo >= hi) break;
+                const size_t n_grp = (hi - lo) / grp;  // whole groups only; a ragged rest stays in place
+                for (size_t a = 0, z = n_grp; a + 1 < z; a++, z--)
+                    std::swap_ranges(pieces.begin() + lo + a * grp, pieces.begin() + lo + (a + 1) * grp, pieces.begin() + lo + (z - 1) * grp);
+            }
+        }
         int32_t *pc = H + p->off_pieces;
         for (const Piece &x : pieces) {
             pc[PP_ITEM] = x.item; pc[PP_T0] = x.t0; pc[PP_T1] = x.t1; pc[PP_SLOT] = x.slot; pc[PP_K] = x.k;
