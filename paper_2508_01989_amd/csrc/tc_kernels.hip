@@ -5,10 +5,13 @@
 //   kv_migrate_kernel  pool <-> contiguous transfer buffer, all layers (paper Sec. 3.5)   (HBM-bound)
 //   mixed_attention_kernel  ONE launch per layer for the whole mixed batch
 //       (paper Sec. 2.2: a prompt chunk plus piggybacked decodes share an iteration):
-//         workgroups [0, n_prefill)      causal chunked-prefill tiles, MFMA 32x32x16 bf16
-//         remaining workgroups           8 independent wavefronts, one decode KV split
-//                                        each, MFMA 16x16x32 bf16
-//   split_merge_kernel combine the split partials of long decode sequences
+//         workgroups [0, n_prefill)      causal chunked-prefill pieces (a row block of 128 rows over a
+//                                        range of 64-token KV tiles), MFMA 32x32x16
+//         remaining workgroups           4 independent wavefronts, one decode KV split each,
+//                                        MFMA 16x16x32 and 16x16x16
+//       168 VGPRs and 48 KiB of LDS: three workgroups per compute unit, so decode workgroups run
+//       beside prefill workgroups.  Instantiated for bf16 and IEEE half.
+//   split_merge_kernel combine the partial results of split decode sequences and of cut prefill row blocks
 //
 // Both attention branches compute S^T = K Q^T and O^T = V^T P^T so that the
 // probabilities a lane produces are exactly the B operand it must feed to the second
@@ -21,7 +24,6 @@
 #include <algorithm>
 
 #include "tc_internal.h"
-
 
 namespace tc {
 
@@ -233,7 +235,7 @@ __global__ void __launch_bounds__(256) kv_migrate_kernel(const MigratePools pool
 }
 
 // ------------------------------------------------------------------------------------
-// Prefill branch: one workgroup = 256 (position, head) rows of one KV head, 32 per wave.
+// Prefill branch: one workgroup = 128 (position, head) rows of one KV head, 32 per wave.
 // ------------------------------------------------------------------------------------
 // Row R of the workgroup is position first_pos + R / G, query head kv_head * G + R % G.
 // The KV range 0..last position is swept in 64-token tiles (four pages); each tile is
