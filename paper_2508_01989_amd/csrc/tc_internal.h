@@ -11,16 +11,14 @@
 namespace tc {
 
 constexpr int kBlock = 16;          // tokens per KV page
-constexpr int kWgThreads = 256;     // threads per workgroup of the fused attention kernel
-constexpr int kWgWaves = kWgThreads / 64;
-#ifndef TC_ROW_BLOCKS
-#define TC_ROW_BLOCKS 1
-#endif
-constexpr int kWaveRowBlocks = TC_ROW_BLOCKS;  // 32-row blocks of a prefill workgroup each wave owns (1 or 2)
-// Workgroups of the fused kernel resident per compute unit: with 32 rows per wave the kernel needs 168
-// VGPRs and 48 KiB of LDS, so three fit; the 64-row variant takes a whole SIMD's registers per wave.
-constexpr int kWgPerCu = kWaveRowBlocks == 1 ? 3 : 1;
-constexpr int kPrefillRows = 32 * kWaveRowBlocks * kWgWaves;  // (position, head) rows per prefill workgroup
+// Launch shapes of the fused attention kernel.  A batch with a prefill chunk runs workgroups of eight
+// waves, one per compute unit (two waves per SIMD, up to 256 registers each): the eight waves sweep the
+// same K/V tiles for 256 (position, head) rows, and a decode workgroup of that launch holds eight
+// independent decode items.  A batch of decodes only runs workgroups of four waves, three per compute unit.
+constexpr int kMixedWaves = 8;
+constexpr int kDecodeWaves = 4;
+constexpr int kDecodeWgPerCu = 3;
+constexpr int kPrefillRows = 32 * kMixedWaves;  // (position, head) rows per prefill workgroup, 32 per wave
 constexpr int kItemInts = 8;        // int32 fields per work item
 constexpr int kAppendInts = 4;      // int32 fields per append segment: first packed row, tokens, first token index, pool block
 constexpr int kMaxSplitPages = 64;  // a decode split's page ids fit one wavefront register
@@ -60,7 +58,8 @@ struct tc_plan {
     int32_t *dev = nullptr;  // device copy of `host`, nullptr for host-only plans
     int device = -1;
 
-    int grid_blocks() const { return n_pieces + (n_decode + tc::kWgWaves - 1) / tc::kWgWaves; }
+    int wg_waves() const { return n_pieces > 0 ? tc::kMixedWaves : tc::kDecodeWaves; }
+    int grid_blocks() const { return n_pieces + (n_decode + wg_waves() - 1) / wg_waves(); }
     size_t workspace_bytes() const {
         // per partial: G heads x (D accumulators + running max + running sum), fp32
         return (size_t)n_partials * (size_t)G * (size_t)(D + 2) * sizeof(float);

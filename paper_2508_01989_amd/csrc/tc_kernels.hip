@@ -5,12 +5,14 @@
 //   kv_migrate_kernel  pool <-> contiguous transfer buffer, all layers (paper Sec. 3.5)   (HBM-bound)
 //   mixed_attention_kernel  ONE launch per layer for the whole mixed batch
 //       (paper Sec. 2.2: a prompt chunk plus piggybacked decodes share an iteration):
-//         workgroups [0, n_prefill)      causal chunked-prefill pieces (a row block of 128 rows over a
-//                                        range of 64-token KV tiles), MFMA 32x32x16
-//         remaining workgroups           4 independent wavefronts, one decode KV split each,
+//         workgroups [0, n_prefill)      causal chunked-prefill pieces: 8 waves = 256 (position, head) rows
+//                                        of one KV head over a range of 64-token KV tiles, MFMA 32x32x16,
+//                                        software-pipelined so that the softmax runs under the MFMAs
+//         remaining workgroups           independent wavefronts, one decode KV split each,
 //                                        MFMA 16x16x32 and 16x16x16
-//       168 VGPRs and 48 KiB of LDS: three workgroups per compute unit, so decode workgroups run
-//       beside prefill workgroups.  Instantiated for bf16 and IEEE half.
+//       Two shapes: 8 waves per workgroup, one workgroup per compute unit, when the batch has a prefill
+//       chunk; 4 waves, three workgroups per compute unit, for a batch of decodes only.
+//       Instantiated for bf16 and IEEE half.
 //   split_merge_kernel combine the partial results of split decode sequences and of cut prefill row blocks
 //
 // Both attention branches compute S^T = K Q^T and O^T = V^T P^T so that the
@@ -22,6 +24,7 @@
 #include <hip/hip_runtime.h>
 
 #include <algorithm>
+#include <type_traits>
 
 #include "tc_internal.h"
 
@@ -251,10 +254,10 @@ struct PrefillCfg {
     static constexpr int kPageBytes = kBlock * D * 2;               // one (page, KV head) tile of K or of V
     static constexpr int kTileBytes = kTilePages * kPageBytes;      // K part or V part of one LDS stage
     static constexpr int kRuns = kPageBytes / 1024;                 // 1 KiB wave-wide loads per page and tensor
-    // Two LDS stages of K (tile t+1 is copied while tile t is used) and one of V: the V tile of an
-    // iteration is copied at its top and awaited, with a barrier of its own, between the softmax and the
-    // second product.  48 KiB at D = 128, so that three workgroups fit the 160 KiB of a compute unit.
-    static constexpr int kLdsBytes = 3 * kTileBytes;
+    // Three LDS stages of K and three of V: a tile is copied two steps before its first use, so the
+    // copies have two whole steps to land.  96 KiB at D = 128.
+    static constexpr int kStages = 3;
+    static constexpr int kLdsBytes = 2 * kStages * kTileBytes;
 };
 
 // N direct-to-LDS loads of 1 KiB each (16 bytes per lane) at immediate offsets 0, 1024, ...
@@ -268,43 +271,55 @@ __device__ __forceinline__ void lds_load_runs(const __attribute__((address_space
     if constexpr (N > 3) __builtin_amdgcn_global_load_lds(src, dst, 16, 3072, 0);
 }
 
-// Tile copies: wave w of the workgroup copies page w of the tile (kWgWaves == pages per tile).
-// Page id of the page this wave copies (a scalar load, issued one tile ahead of its use).
+// Page id of page `page_in_tile` of KV tile `tile` (a scalar load; past the end of the sequence the
+// last page is named, whose copy is never used).
 template <int D>
-__device__ __forceinline__ int prefill_page_id(const int32_t *__restrict__ pages, int n_pages, int tile, int wave) {
-    return pages[min(tile * PrefillCfg<D>::kTilePages + wave, n_pages - 1)];
+__device__ __forceinline__ int prefill_page_id(const int32_t *__restrict__ pages, int n_pages, int tile, int page_in_tile) {
+    return pages[min(tile * PrefillCfg<D>::kTilePages + page_in_tile, n_pages - 1)];
 }
 
-// Copy one page of K and of V^T (one KV head) from the pool straight into an LDS stage with
-// direct-to-LDS loads: lane L deposits its 16 bytes at (wave-uniform base) + 16 L, so each load
-// copies a 1 KiB run; the runs of a page are contiguous both in the pool and in LDS, so they share
-// one address register and one LDS base and differ only in the instruction's immediate offset.
-// K pages are copied verbatim.  A V^T page is copied row by row (32 bytes = 16 token slots of one
-// head-dim element) with the two 16-byte halves of rows 8-15 (mod 16) exchanged, so that the
-// operand reads of 16 consecutive rows cover all 64 LDS banks (a 1 KiB step is 32 rows, so the
-// exchange pattern is the same in every run).
+// Tile copies.  The 8 waves of a workgroup share every tile: waves 0-3 copy the four K pages of a
+// tile, waves 4-7 its four V^T pages, each with direct-to-LDS loads: lane L deposits its 16 bytes at
+// (wave-uniform base) + 16 L, so each load copies a 1 KiB run; the runs of a page are contiguous both
+// in the pool and in LDS, so they share one address register and one LDS base and differ only in the
+// instruction's immediate offset.  K pages are copied verbatim.  A V^T page is copied row by row
+// (32 bytes = 16 token slots of one head-dim element) with the two 16-byte halves of rows 8-15
+// (mod 16) exchanged, so that the operand reads of 16 consecutive rows cover all 64 LDS banks (a
+// 1 KiB step is 32 rows, so the exchange pattern is the same in every run).
 template <int D>
-__device__ __forceinline__ void prefill_fetch(const AttnArgs &A, int kvh, int page_id, char *lds_k, char *lds_v, int wave,
-                                              int lane) {
+struct TileCopier {
     using C = PrefillCfg<D>;
-    static_assert(C::kTilePages == kWgWaves, "one wave per page of a tile");
-    static_assert(C::kTileTokens == kPrefillTileTokens, "the planner cuts KV ranges in units of this tile");
     typedef const __attribute__((address_space(1))) void *gptr_t;
     typedef __attribute__((address_space(3))) void *lptr_t;
-    const int64_t base = ((int64_t)__builtin_amdgcn_readfirstlane(page_id) * A.Hkv + kvh) * (int64_t)(kBlock * D);
-    const int d = lane >> 1, half = (lane & 1) ^ ((d >> 3) & 1);
-    const gptr_t ksrc = (gptr_t)(A.k_pool + base + lane * 8);
-    const gptr_t vsrc = (gptr_t)(A.v_pool + base + d * kBlock + half * 8);
-    const lptr_t kdst = (lptr_t)(lds_k + wave * C::kPageBytes);
-    const lptr_t vdst = (lptr_t)(lds_v + wave * C::kPageBytes);
-    if (lds_k) lds_load_runs<C::kRuns>(ksrc, kdst);
-    if (lds_v) lds_load_runs<C::kRuns>(vsrc, vdst);
-}
+    const uint16_t *src;  // pool + this lane's element offset inside a (page, KV head) block
+    char *dst;            // stage 0 of this wave's tensor + its page slot
+    int64_t head_off;     // kv head * block elements
+    int64_t page_stride;  // elements per page (all KV heads)
+    bool is_v;
+    int page_in_tile;
+    __device__ __forceinline__ TileCopier(const AttnArgs &A, int kvh, char *lds_k, char *lds_v, int wave, int lane) {
+        static_assert(2 * C::kTilePages == kMixedWaves, "one wave per page of a tile and tensor");
+        static_assert(C::kTileTokens == kPrefillTileTokens, "the planner cuts KV ranges in units of this tile");
+        is_v = wave >= C::kTilePages;
+        page_in_tile = wave & (C::kTilePages - 1);
+        const int d = lane >> 1, half = (lane & 1) ^ ((d >> 3) & 1);
+        src = is_v ? A.v_pool + d * kBlock + half * 8 : A.k_pool + lane * 8;
+        dst = (is_v ? lds_v : lds_k) + page_in_tile * C::kPageBytes;
+        head_off = (int64_t)kvh * (kBlock * D);
+        page_stride = (int64_t)A.Hkv * (kBlock * D);
+    }
+    // copy this wave's page (wave-uniform id) into LDS stage `stage` of its tensor
+    __device__ __forceinline__ void copy(int page_id, int stage) const {
+        const int64_t base = (int64_t)__builtin_amdgcn_readfirstlane(page_id) * page_stride + head_off;
+        lds_load_runs<C::kRuns>((gptr_t)(src + base), (lptr_t)(dst + stage * C::kTileBytes));
+    }
+};
 
 // After this thread's own direct-to-LDS loads of `tile` have landed: slots at or past `kv_len`
 // hold undefined bits (the tail of the last page, or a clamped re-read of it for pages past the
 // end).  They get probability 0 but must be finite for the MFMA, so zero them in the V stage.
-// Each thread patches only the 16-byte pieces it loaded itself, so no extra barrier is needed.
+// Each thread patches only the 16-byte pieces it loaded itself (`wave` = the page of the tile this
+// wave copied), so no extra barrier is needed.
 template <int D>
 __device__ __forceinline__ void prefill_fix_tail(char *lds_v, int tile, int wave, int lane, int kv_len) {
     using C = PrefillCfg<D>;
@@ -329,6 +344,21 @@ __device__ __forceinline__ void prefill_fix_tail(char *lds_v, int tile, int wave
 
 __device__ __forceinline__ void wait_all_loads() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); }
 
+// A page id fetched with a vector load, so that it is counted by vmcnt like the tile copies and the
+// LDS operand reads keep exact lgkmcnt waits (a scalar load in flight would force them to wait for
+// everything).  page_id_issue starts the load; the value may be used only after page_id_wait, which
+// also waits for every tile copy issued before the page id load (loads return in order).
+__device__ __forceinline__ int page_id_issue(const int32_t *p) {
+    int v;
+    asm volatile("global_load_dword %0, %1, off" : "=v"(v) : "v"(p) : "memory");
+    return v;
+}
+template <int N>  // N = loads issued after the page id load that may stay in flight
+__device__ __forceinline__ int page_id_wait(int v) {
+    asm volatile("s_waitcnt vmcnt(%1)" : "+v"(v) : "n"(N) : "memory");
+    return __builtin_amdgcn_readfirstlane(v);
+}
+
 // max / sum across the two half-waves (lanes l and l ^ 32 hold the two halves of a row).
 __device__ __forceinline__ float half_swap_max(float v) {
     const auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(v), __float_as_uint(v), false, false);
@@ -339,15 +369,94 @@ __device__ __forceinline__ float half_swap_sum(float v) {
     return __uint_as_float(r[0]) + __uint_as_float(r[1]);
 }
 
+// One wave's share of the two products and of the softmax, for 32 rows x 32 tokens (half a tile).
+template <int D, class E>
+struct PrefillWave {
+    using C = PrefillCfg<D>;
+    using x8 = typename E::x8;
+    using el = typename E::t;
+    static constexpr int KS = D / 16;  // k-steps of the QK^T product
+    static constexpr int MT = D / 32;  // 32-row tiles of O^T
+
+    // K fragments (MFMA A operands) of tokens 32 h .. 32 h + 31 of a K stage; kp = stage base + lane offset.
+    typedef const __attribute__((address_space(3))) char *lds_cptr;
+    typedef const __attribute__((address_space(3))) x8 *lds_x8ptr;
+    static __device__ __forceinline__ void load_k(lds_cptr kp, int h, x8 (&kf)[KS]) {
+#pragma unroll
+        for (int kk = 0; kk < KS; kk++) kf[kk] = *(lds_x8ptr)(kp + 2 * h * C::kPageBytes + 2 * kk * (kBlock * 16));
+    }
+    // V^T fragments of the two pages of half h of a V stage; vp = stage base + lane offset.
+    static __device__ __forceinline__ void load_v(lds_cptr vp, int h, x8 (&vf)[2][MT]) {
+#pragma unroll
+        for (int b = 0; b < 2; b++)
+#pragma unroll
+            for (int c = 0; c < MT; c++) vf[b][c] = *(lds_x8ptr)(vp + (2 * h + b) * C::kPageBytes + c * (32 * 32));
+    }
+    // S^T = K Q^T for 32 tokens
+    static __device__ __forceinline__ void qk(const x8 (&kf)[KS], const x8 (&qreg)[KS], f32x16 &s) {
+#pragma unroll
+        for (int r = 0; r < 16; r++) s[r] = 0.f;
+#pragma unroll
+        for (int kk = 0; kk < KS; kk++) s = E::mfma32(kf[kk], qreg[kk], s);
+    }
+    // Scores of tokens past the row's own position become -inf (probability 0); tok0 = first token of the half.
+    static __device__ __forceinline__ void causal_mask(f32x16 &s, int tok0, int hh, int p_abs) {
+#pragma unroll
+        for (int r = 0; r < 16; r++) {
+            const int j = tok0 + 8 * (r >> 2) + 4 * hh + (r & 3);
+            s[r] = (j <= p_abs) ? s[r] : -INFINITY;
+        }
+    }
+    // Row maximum over the 32 tokens (both half-waves).
+    static __device__ __forceinline__ float row_max(const f32x16 &s) {
+        float mx = s[0];
+#pragma unroll
+        for (int r = 1; r < 16; r++) mx = fmaxf(mx, s[r]);
+        return half_swap_max(mx);
+    }
+    // p = 2^(s * c - m), rounded to the element type as the B operand of the second product (one
+    // operand per page); the row sum accumulates the unrounded values.  (Summing the rounded pairs with
+    // one dot-product instruction per pair measured 9 % slower.)
+    static __device__ __forceinline__ void probs(const f32x16 &s, float c_log2, float m_run, x8 (&pb)[2], float &l_run) {
+        float psum = 0.f;
+#pragma unroll
+        for (int b = 0; b < 2; b++)
+#pragma unroll
+            for (int e = 0; e < 8; e++) {
+                const float pv = fast_exp2(__builtin_fmaf(s[8 * b + e], c_log2, -m_run));
+                psum += pv;
+                pb[b][e] = (el)pv;
+            }
+        l_run += psum;
+    }
+    // O^T += V^T P^T over 32 tokens
+    static __device__ __forceinline__ void pv(const x8 (&vf)[2][MT], const x8 (&pb)[2], f32x16 (&o)[MT]) {
+#pragma unroll
+        for (int b = 0; b < 2; b++)
+#pragma unroll
+            for (int c = 0; c < MT; c++) o[c] = E::mfma32(vf[b][c], pb[b], o[c]);
+    }
+};
+
+// The KV sweep is software-pipelined inside every wave, in units of half a tile (32 tokens), three
+// halves deep: in one phase the matrix cores compute the scores of half h + 1 and accumulate P V of
+// half h - 1 while the vector ALU turns the scores of half h into probabilities.  (MFMA and VALU
+// instructions of one wave overlap fully when they are interleaved in the instruction stream;
+// executed one after the other their times add up.)  The LDS read that refills an MFMA's operand
+// register for the next phase follows that MFMA, a whole phase ahead of its use.  The 8 waves share
+// the K/V tiles; a tile is copied two steps ahead of its first use, so one barrier per tile suffices
+// and no wave waits for a copy:
+//   step j:  barrier | copy K(j+3) (waves 0-3), V(j+2) (waves 4-7) | phase 2j | phase 2j + 1
+//            | wait for the copies this wave issued in step j - 1
 template <int D, class E>
 __device__ void prefill_item(const AttnArgs &A, const int32_t *__restrict__ it, const int32_t *__restrict__ pc, char *lds) {
     using C = PrefillCfg<D>;
+    using W = PrefillWave<D, E>;
     using x8 = typename E::x8;
     using x4 = typename E::x4;
     using el = typename E::t;
-    constexpr int KS = D / 16;      // k-steps of the QK^T product
-    constexpr int MT = D / 32;      // 32-row tiles of O^T
-    constexpr int RB = kWaveRowBlocks;  // 32-row blocks per wave: every K / V fragment read from LDS feeds RB MFMAs
+    typedef typename W::lds_cptr lds_cptr;
+    constexpr int KS = W::KS, MT = W::MT;
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int n = lane & 31, hh = lane >> 5;
@@ -356,185 +465,195 @@ __device__ void prefill_item(const AttnArgs &A, const int32_t *__restrict__ it, 
     const int32_t *pages = A.pages + it[PF_PAGEOFF];
     const int G = A.G;
     const int n_rows = npos * G;
-    // Row block rb of this wave holds workgroup rows wave*32*RB + rb*32 .. +31; this lane's row of it:
-    bool row_valid[RB];
-    int Rc[RB], p_abs[RB];  // clamped row; absolute position: the row attends over tokens 0..p_abs
-    int64_t row_off[RB];
-#pragma unroll
-    for (int rb = 0; rb < RB; rb++) {
-        const int R = (wave * RB + rb) * 32 + n;
-        row_valid[rb] = R < n_rows;
-        Rc[rb] = row_valid[rb] ? R : n_rows - 1;
-        const int pl = pos0 + Rc[rb] / G;
-        p_abs[rb] = ctx + pl;
-        row_off[rb] = ((int64_t)(qrow0 + pl) * A.Hq + kvh * G + Rc[rb] % G) * D;
-    }
-    // wave-uniform bounds of the rows this wave owns
-    const int r_lo = min(wave * 32 * RB, n_rows - 1), r_hi = min(wave * 32 * RB + 32 * RB - 1, n_rows - 1);
-    const int wave_pmin = ctx + pos0 + r_lo / G, wave_pmax = ctx + pos0 + r_hi / G;
+    // this lane's row of the workgroup's 256: position pos0 + R / G, head kvh * G + R % G
+    const int R = wave * 32 + n;
+    const bool row_valid = R < n_rows;
+    const int Rc = row_valid ? R : n_rows - 1;
+    const int p_abs = ctx + pos0 + Rc / G;  // the row attends over tokens 0..p_abs
+    const int64_t row_off = ((int64_t)(qrow0 + pos0 + Rc / G) * A.Hq + kvh * G + Rc % G) * D;
+    // first position of the rows this wave owns (wave-uniform): tiles that end at or before it need no mask
+    const int wave_pmin = ctx + pos0 + min(wave * 32, n_rows - 1) / G;
     const int kv_len = ctx + pos0 + npos;  // tokens this workgroup may read (all appended already)
     // KV tiles [t_begin, t_end) of the item; p_slot < 0: the whole range, results go to `out`
     const int t_begin = pc[PP_T0], t_end = pc[PP_T1], p_slot = pc[PP_SLOT], p_k = pc[PP_K];
+    const int n_sweep = t_end - t_begin;
     const float c_log2 = A.scale_log2;
-    const int v_lane_off = n * 32 + ((hh ^ ((n >> 3) & 1)) * 16);  // this lane's 16 bytes inside a 32-row V^T tile
+    char *const lds_k = lds, *const lds_v = lds + C::kStages * C::kTileBytes;
+    // per-lane byte offsets of the MFMA A operands inside a stage
+    const int k_lane_off = (n >> 4) * C::kPageBytes + (n & 15) * 16 + hh * (kBlock * 16);
+    const int v_lane_off = n * 32 + ((hh ^ ((n >> 3) & 1)) * 16);
 
-    x8 qreg[RB][KS];
+    x8 qreg[KS];
 #pragma unroll
-    for (int rb = 0; rb < RB; rb++)
-#pragma unroll
-        for (int kk = 0; kk < KS; kk++) qreg[rb][kk] = *reinterpret_cast<const x8 *>(A.q + row_off[rb] + (2 * kk + hh) * 8);
+    for (int kk = 0; kk < KS; kk++) qreg[kk] = *reinterpret_cast<const x8 *>(A.q + row_off + (2 * kk + hh) * 8);
 
-    f32x16 o[RB][MT];
-    float m_run[RB], l_run[RB];  // running row maximum (log2 domain) and row sum (this half-wave's share)
+    f32x16 o[MT];
 #pragma unroll
-    for (int rb = 0; rb < RB; rb++) {
-        m_run[rb] = -1e30f;
-        l_run[rb] = 0.f;
+    for (int c = 0; c < MT; c++)
+#pragma unroll
+        for (int r = 0; r < 16; r++) o[c][r] = 0.f;
+    float m_run = -1e30f;  // running row maximum (log2 domain)
+    float l_run = 0.f;     // running sum of this lane's half of the row
+
+    // ---- prologue: tile j of the sweep lives in stage j mod 3 of its tensor.  K(0..2) and V(0..1) are
+    // copied here; step j then copies K(j+3) and V(j+2).  `ahead` = how far this wave's copy of a step
+    // runs ahead of the step's own tile.
+    const TileCopier<D> cp(A, kvh, lds_k, lds_v, wave, lane);
+    const int ahead = cp.is_v ? 2 : 3;
+    cp.copy(prefill_page_id<D>(pages, n_pages, t_begin, cp.page_in_tile), 0);
+    cp.copy(prefill_page_id<D>(pages, n_pages, t_begin + 1, cp.page_in_tile), 1);
+    if (!cp.is_v) cp.copy(prefill_page_id<D>(pages, n_pages, t_begin + 2, cp.page_in_tile), 2);
+    int id_cur = prefill_page_id<D>(pages, n_pages, t_begin + ahead, cp.page_in_tile);  // page this wave copies in step 0
+    wait_all_loads();
+    if (cp.is_v) {
+        if ((t_begin + 1) * C::kTileTokens > kv_len) prefill_fix_tail<D>(lds_v, t_begin, cp.page_in_tile, lane, kv_len);
+        if ((t_begin + 2) * C::kTileTokens > kv_len) prefill_fix_tail<D>(lds_v + C::kTileBytes, t_begin + 1, cp.page_in_tile, lane, kv_len);
+    }
+    __syncthreads();
+    x8 kf[KS];     // K fragments of the half whose scores are computed next
+    x8 vf[2][MT];  // V^T fragments of the half whose P V product comes next
+    x8 pb[2];      // probabilities of that half (B operands, one per page)
+    f32x16 sc, sn;
+    W::load_k((lds_cptr)(lds_k + k_lane_off), 0, kf);
+    W::qk(kf, qreg, sc);
+    W::load_k((lds_cptr)(lds_k + k_lane_off), 1, kf);
+    // the first phase has no earlier half to accumulate: give its P V product zero probabilities
+    W::load_v((lds_cptr)(lds_v + v_lane_off), 0, vf);
+#pragma unroll
+    for (int b = 0; b < 2; b++)
+#pragma unroll
+        for (int e = 0; e < 8; e++) pb[b][e] = (el)0.f;
+    if (t_begin * C::kTileTokens + 31 > wave_pmin) W::causal_mask(sc, t_begin * C::kTileTokens, hh, p_abs);
+    float m_new = fmaxf(m_run, W::row_max(sc) * c_log2);
+    float alpha_o = 1.f;  // factor O still has to be multiplied with before the next P V product
+
+    // One phase, for half-tile h: `cur` holds its scores S(h) (their maxima already in m_new), `kf` the K
+    // fragments of half h + 1, `vf` / `pb` the V^T fragments and probabilities of half h - 1.
+    //   matrix cores:  S(h+1) = K(h+1) Q^T  (QK),   O += V(h-1)^T P(h-1)^T
+    //   vector ALU:    P(h) = 2^(S(h) c - m)  under those MFMAs, then the row maxima of S(h+1)
+    //   LDS:           every MFMA is followed by the read that refills its operand register for the next
+    //                  phase: K fragments of half h + 2 (KREAD), V^T fragments of half h
+    // O is relative to the maximum its last product used; the factor that brings it to the current one is
+    // applied (rarely, wave-uniform branch) just before the next product.
+    // MASK: half h + 1 may reach past a row's own position or past the last token.  Without MASK the
+    // phase is, apart from that branch, one straight line of code.
+    auto phase = [&](lds_cptr v_h, int hv, lds_cptr k_after, int hk, f32x16 &cur, f32x16 &nxt, int tok_nxt, auto mask_tag,
+                     auto qk_tag, auto kread_tag) {
+        constexpr bool MASK = decltype(mask_tag)::value, QK = decltype(qk_tag)::value, KREAD = decltype(kread_tag)::value;
+        if (__builtin_amdgcn_ballot_w64(alpha_o != 1.f) != 0) {
+#pragma unroll
+            for (int c = 0; c < MT; c++)
+#pragma unroll
+                for (int r = 0; r < 16; r++) o[c][r] *= alpha_o;
+        }
+        alpha_o = fast_exp2(m_run - m_new);  // 1 unless this row's maximum moved
+        m_run = m_new;
+        l_run *= alpha_o;
+        if (QK) W::qk(kf, qreg, nxt);
+        if (KREAD) W::load_k(k_after, hk, kf);
+        W::pv(vf, pb, o);
+        W::load_v(v_h, hv, vf);
+        W::probs(cur, c_log2, m_run, pb, l_run);
+        if (MASK && QK) W::causal_mask(nxt, tok_nxt, hh, p_abs);
+        if (QK) m_new = fmaxf(m_run, W::row_max(nxt) * c_log2);
+        // the probabilities are used by the next phase: have them computed in this one
+        asm volatile("" : "+v"(pb[0]), "+v"(pb[1]), "+v"(l_run), "+v"(m_new));
+        if (!MASK && QK && KREAD) {
+            // per MFMA: the read that refills its operand, then softmax work, two elements at a time (spreading
+            // it evenly over all MFMAs of the phase measured 6 % slower); the row maxima of the new scores go
+            // under the last MFMAs of the second product
+            constexpr int kMfma = KS + 2 * MT;
+#pragma unroll
+            for (int g = 0; g < kMfma; g++) {
+                __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+                __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+                if (g < kMfma - 4) {
+                    __builtin_amdgcn_sched_group_barrier(0x002, (16 + kMfma - 5) / (kMfma - 4), 0);
+                    __builtin_amdgcn_sched_group_barrier(0x400, (16 + kMfma - 5) / (kMfma - 4), 0);
+                    __builtin_amdgcn_sched_group_barrier(0x002, (24 + kMfma - 5) / (kMfma - 4), 0);
+                } else {
+                    __builtin_amdgcn_sched_group_barrier(0x002, 4, 0);
+                }
+            }
+        }
+    };
+    // One step for tile t_begin + j, which lives in stage s0 = j mod 3: `sc` holds the scores of its first
+    // half, `kf` the K fragments of its second half.  NEXT: tile j + 1 exists.
+    int s0 = 0;
+    auto step = [&](int j, auto mask_tag, auto next_tag) {
+        constexpr bool NEXT = decltype(next_tag)::value;
+        const int tile = t_begin + j;
+        const int s1 = s0 == C::kStages - 1 ? 0 : s0 + 1, s2 = s1 == C::kStages - 1 ? 0 : s1 + 1;
+        lds_cptr k_nxt = (lds_cptr)(lds_k + s1 * C::kTileBytes + k_lane_off);
+        lds_cptr v_cur = (lds_cptr)(lds_v + s0 * C::kTileBytes + v_lane_off);
+        // have both operand addresses in registers here, outside the scheduled regions below
+        asm volatile("" : "+v"(k_nxt), "+v"(v_cur));
+        __syncthreads();  // every wave is done with step j - 1; the copies issued in step j - 2 are visible
+        int id_nxt = 0;
+        if (NEXT) {
+            // first the page id for the next step's copy, then this step's copy: K(j+3) replaces K(j),
+            // V(j+2) replaces V(j-1).  Past the end of the range the page index is clamped and the copy
+            // is never read.
+            id_nxt = page_id_issue(pages + min((tile + 1 + ahead) * C::kTilePages + cp.page_in_tile, n_pages - 1));
+            cp.copy(id_cur, cp.is_v ? s2 : s0);
+        }
+        const std::true_type yes;
+        phase(v_cur, 0, k_nxt, 0, sc, sn, tile * C::kTileTokens + 32, mask_tag, yes, next_tag);
+        phase(v_cur, 1, k_nxt, 1, sn, sc, (tile + 1) * C::kTileTokens, mask_tag, next_tag, next_tag);
+        if (NEXT) {
+            // everything but this step's copy has landed: the next page id and the copies of step j - 1
+            id_cur = page_id_wait<C::kRuns>(id_nxt);
+            if (decltype(mask_tag)::value && cp.is_v && (tile + 2) * C::kTileTokens > kv_len)
+                prefill_fix_tail<D>(lds_v + s1 * C::kTileBytes, tile + 1, cp.page_in_tile, lane, kv_len);
+        }
+        s0 = s1;
+    };
+    {
+        const std::true_type yes;
+        const std::false_type no;
+        // steps 0 .. n_plain - 1 prepare tiles that lie wholly at or before every row's position
+        // and before the last token: tile t needs no mask if (t + 1) * 64 - 1 <= wave_pmin
+        const int n_plain = max(0, min(n_sweep - 1, (wave_pmin + 1) / C::kTileTokens - t_begin - 1));
+        int j = 0;
+        for (; j < n_plain; j++) step(j, no, yes);
+        for (; j + 1 < n_sweep; j++) step(j, yes, yes);
+        step(j, yes, no);
+    }
+    // the product of the last half
+#pragma unroll
+    for (int c = 0; c < MT; c++)
+#pragma unroll
+        for (int r = 0; r < 16; r++) o[c][r] *= alpha_o;
+    W::pv(vf, pb, o);
+
+    const float l = half_swap_sum(l_run);
+    if (!row_valid) return;
+    if (p_slot >= 0) {
+        // A piece of a cut item: unnormalised accumulators, running maximum (log2 domain) and row sum
+        // go to the workspace, in the partial layout the decode splits use; rows that see no key of
+        // this piece carry (m, l, o) = (-1e30, 0, 0) and get weight 0 in the merge.
+        const int64_t prow = ((int64_t)(p_slot + (Rc / G) * p_k)) * G + Rc % G;
+        float *dst = A.ws_o + prow * D + 4 * hh;
 #pragma unroll
         for (int c = 0; c < MT; c++)
 #pragma unroll
-            for (int r = 0; r < 16; r++) o[rb][c][r] = 0.f;
-    }
-
-    char *const v_lds = lds + 2 * C::kTileBytes;
-    int page_id = prefill_page_id<D>(pages, n_pages, t_begin, wave);
-    int page_v = page_id;  // page whose V this wave copies at the top of the next iteration
-    prefill_fetch<D>(A, kvh, page_id, lds, nullptr, wave, lane);
-    page_id = prefill_page_id<D>(pages, n_pages, t_begin + 1, wave);
-    wait_all_loads();
-    __syncthreads();
-
-    for (int tile = t_begin; tile < t_end; tile++) {
-        const int cur = (tile - t_begin) & 1;
-        const char *ks = lds + cur * C::kTileBytes;
-        const char *vs = v_lds;
-        const bool more = tile + 1 < t_end;
-        // The V buffer and K stage cur^1 were last read before the barrier that ended the previous
-        // iteration: copy this tile's V (needed after the softmax) and the next tile's K.
-        prefill_fetch<D>(A, kvh, page_v, nullptr, v_lds, wave, lane);
-        page_v = page_id;
-        if (more) {
-            prefill_fetch<D>(A, kvh, page_id, lds + (cur ^ 1) * C::kTileBytes, nullptr, wave, lane);
-            page_id = prefill_page_id<D>(pages, n_pages, tile + 2, wave);
+            for (int q4 = 0; q4 < 4; q4++)
+                *reinterpret_cast<f32x4 *>(dst + 32 * c + 8 * q4) = f32x4{o[c][4 * q4], o[c][4 * q4 + 1], o[c][4 * q4 + 2], o[c][4 * q4 + 3]};
+        if (hh == 0) {
+            A.ws_ml[prow * 2] = m_run;
+            A.ws_ml[prow * 2 + 1] = l;
         }
-
-        const int tok0 = tile * C::kTileTokens;
-        const bool active = tok0 <= wave_pmax;  // otherwise every (row, token) pair of this wave is masked
-        f32x16 s[RB][2];
-        if (active) {
+    } else {
+        const float inv = 1.f / l;
 #pragma unroll
-            for (int mt = 0; mt < 2; mt++) {
+        for (int c = 0; c < MT; c++)
 #pragma unroll
-                for (int rb = 0; rb < RB; rb++)
+            for (int q4 = 0; q4 < 4; q4++) {
+                x4 w;
 #pragma unroll
-                    for (int r = 0; r < 16; r++) s[rb][mt][r] = 0.f;
-                const char *kp = ks + (2 * mt + (n >> 4)) * C::kPageBytes + (n & 15) * 16;
-#pragma unroll
-                for (int kk = 0; kk < KS; kk++) {
-                    const x8 a = *reinterpret_cast<const x8 *>(kp + (2 * kk + hh) * (kBlock * 16));
-#pragma unroll
-                    for (int rb = 0; rb < RB; rb++) s[rb][mt] = E::mfma32(a, qreg[rb][kk], s[rb][mt]);
-                }
+                for (int e = 0; e < 4; e++) w[e] = (el)(o[c][4 * q4 + e] * inv);
+                *reinterpret_cast<x4 *>(A.out + row_off + 32 * c + 8 * q4 + 4 * hh) = w;
             }
-            if (tok0 + C::kTileTokens - 1 > wave_pmin) {  // the diagonal crosses this tile: causal mask
-#pragma unroll
-                for (int rb = 0; rb < RB; rb++)
-#pragma unroll
-                    for (int mt = 0; mt < 2; mt++)
-#pragma unroll
-                        for (int r = 0; r < 16; r++) {
-                            const int j = tok0 + 32 * mt + 8 * (r >> 2) + 4 * hh + (r & 3);
-                            s[rb][mt][r] = (j <= p_abs[rb]) ? s[rb][mt][r] : -INFINITY;
-                        }
-            }
-#pragma unroll
-            for (int rb = 0; rb < RB; rb++) {
-                float mx = s[rb][0][0];
-#pragma unroll
-                for (int mt = 0; mt < 2; mt++)
-#pragma unroll
-                    for (int r = 0; r < 16; r++) mx = fmaxf(mx, s[rb][mt][r]);
-                mx = half_swap_max(mx);
-                const float m_new = fmaxf(m_run[rb], mx * c_log2);
-                if (__builtin_amdgcn_ballot_w64(m_new > m_run[rb]) != 0) {  // some row's maximum moved: rescale
-                    const float alpha = fast_exp2(m_run[rb] - m_new);
-                    m_run[rb] = m_new;
-                    l_run[rb] *= alpha;
-#pragma unroll
-                    for (int c = 0; c < MT; c++)
-#pragma unroll
-                        for (int r = 0; r < 16; r++) o[rb][c][r] *= alpha;
-                }
-                float psum = 0.f;
-#pragma unroll
-                for (int mt = 0; mt < 2; mt++)
-#pragma unroll
-                    for (int r = 0; r < 16; r++) {
-                        const float pv = fast_exp2(__builtin_fmaf(s[rb][mt][r], c_log2, -m_run[rb]));
-                        s[rb][mt][r] = pv;
-                        psum += pv;
-                    }
-                l_run[rb] += psum;
-            }
-        }
-        // This iteration's V tile: this wave's own copy has landed (the K loads issued after it may still
-        // be in flight); patch the tail, then every wave's part is visible after the barrier.
-        if (more) asm volatile("s_waitcnt vmcnt(%0)" ::"n"(C::kRuns) : "memory");
-        else wait_all_loads();
-        if ((tile + 1) * C::kTileTokens > kv_len) prefill_fix_tail<D>(v_lds, tile, wave, lane, kv_len);
-        __syncthreads();
-        if (active) {
-#pragma unroll
-            for (int b = 0; b < C::kTilePages; b++) {
-                x8 pb[RB];
-#pragma unroll
-                for (int rb = 0; rb < RB; rb++)
-#pragma unroll
-                    for (int e = 0; e < 8; e++) pb[rb][e] = (el)s[rb][b >> 1][8 * (b & 1) + e];
-#pragma unroll
-                for (int c = 0; c < MT; c++) {
-                    const x8 a = *reinterpret_cast<const x8 *>(vs + b * C::kPageBytes + c * (32 * 32) + v_lane_off);
-#pragma unroll
-                    for (int rb = 0; rb < RB; rb++) o[rb][c] = E::mfma32(a, pb[rb], o[rb][c]);
-                }
-            }
-        }
-        wait_all_loads();  // the next tile's K
-        __syncthreads();
-    }
-
-#pragma unroll
-    for (int rb = 0; rb < RB; rb++) {
-        const float l = half_swap_sum(l_run[rb]);
-        if (!row_valid[rb]) continue;
-        if (p_slot >= 0) {
-            // A piece of a cut item: unnormalised accumulators, running maximum (log2 domain) and row sum
-            // go to the workspace, in the partial layout the decode splits use; rows that see no key of
-            // this piece carry (m, l, o) = (-1e30, 0, 0) and get weight 0 in the merge.
-            const int64_t prow = ((int64_t)(p_slot + (Rc[rb] / G) * p_k)) * G + Rc[rb] % G;
-            float *dst = A.ws_o + prow * D + 4 * hh;
-#pragma unroll
-            for (int c = 0; c < MT; c++)
-#pragma unroll
-                for (int q4 = 0; q4 < 4; q4++)
-                    *reinterpret_cast<f32x4 *>(dst + 32 * c + 8 * q4) =
-                        f32x4{o[rb][c][4 * q4], o[rb][c][4 * q4 + 1], o[rb][c][4 * q4 + 2], o[rb][c][4 * q4 + 3]};
-            if (hh == 0) {
-                A.ws_ml[prow * 2] = m_run[rb];
-                A.ws_ml[prow * 2 + 1] = l;
-            }
-        } else {
-            const float inv = 1.f / l;
-#pragma unroll
-            for (int c = 0; c < MT; c++)
-#pragma unroll
-                for (int q4 = 0; q4 < 4; q4++) {
-                    x4 w;
-#pragma unroll
-                    for (int e = 0; e < 4; e++) w[e] = (el)(o[rb][c][4 * q4 + e] * inv);
-                    *reinterpret_cast<x4 *>(A.out + row_off[rb] + 32 * c + 8 * q4 + 4 * hh) = w;
-                }
-        }
     }
 }
 
@@ -546,9 +665,10 @@ __device__ void prefill_item(const AttnArgs &A, const int32_t *__restrict__ it, 
 //   S^T[token][head] = sum_d K[token][d] Q[head][d]   16x16x32, D/32 steps; lane gets tokens 4g..4g+3
 //   O^T[d][head]    += sum_token V^T[d][token] P^T[token][head]   16x16x16, contraction over the page's
 //                      16 tokens: lane feeds tokens 4g..4g+3
-// Pages resident in registers per wave: one being consumed, the rest in flight.  Two keep the whole
-// kernel within 168 VGPRs (three waves per SIMD); three or four measured the same bandwidth.
-constexpr int kDecodeStages = 2;
+// Pages resident in registers per wave (NS): one being consumed, the rest in flight.  A decode-only
+// launch runs twelve waves per compute unit and keeps two (168 VGPRs, three waves per SIMD; more measured
+// the same bandwidth); a mixed launch runs eight waves per compute unit with up to 256 registers each and
+// keeps four, so that its fewer waves have as many bytes in flight.
 
 template <int D>
 struct DecodePage {  // K and V of one page, in MFMA A-operand registers
@@ -617,14 +737,13 @@ __device__ __forceinline__ void decode_consume(const AttnArgs &A, DecodePage<D> 
     }
 }
 
-template <int D, class E>
+template <int D, class E, int NS>
 __device__ void decode_item(const AttnArgs &A, const int32_t *__restrict__ it) {
     using x8 = typename E::x8;
     using x4 = typename E::x4;
     using el = typename E::t;
     constexpr int KS = D / 32;  // k-steps of K Q^T
     constexpr int MT = D / 16;  // 16-row tiles of O^T
-    constexpr int NS = kDecodeStages;
     const int lane = threadIdx.x & 63;
     const int j = lane & 15, g = lane >> 4;
     const int kvh = it[DC_KVH], t0 = it[DC_BEGIN], t1 = it[DC_END], qrow = it[DC_QROW], slot = it[DC_SLOT];
@@ -699,9 +818,10 @@ struct AttnScalars {
 
 // The pointers are separate __restrict__ kernel arguments (not struct members) so that the
 // compiler knows the work list and the page table are never written and can fetch them with
-// scalar loads.
-template <int D, class E>
-__global__ void __launch_bounds__(kWgThreads, kWgPerCu)
+// scalar loads.  WAVES = 8: batches with a prefill chunk (one workgroup per compute unit, up to 256
+// registers per wave); WAVES = 4: decode-only batches (three workgroups per compute unit).
+template <int D, class E, int WAVES>
+__global__ void __launch_bounds__(WAVES * 64, WAVES == kMixedWaves ? 1 : kDecodeWgPerCu)
     mixed_attention_kernel(const uint16_t *__restrict__ k_pool, const uint16_t *__restrict__ v_pool,
                            const uint16_t *__restrict__ q, uint16_t *__restrict__ out, const int32_t *__restrict__ pages,
                            const int32_t *__restrict__ prefill, const int32_t *__restrict__ pieces,
@@ -713,13 +833,15 @@ __global__ void __launch_bounds__(kWgThreads, kWgPerCu)
     A.ws_o = ws_o; A.ws_ml = ws_ml;
     A.n_prefill = sc.n_prefill; A.n_decode = sc.n_decode; A.Hq = sc.Hq; A.Hkv = sc.Hkv; A.G = sc.G;
     A.scale_log2 = sc.scale_log2;
-    if ((int)blockIdx.x < A.n_prefill) {
-        const int32_t *pc = pieces + (int64_t)blockIdx.x * kItemInts;
-        prefill_item<D, E>(A, prefill + (int64_t)pc[PP_ITEM] * kItemInts, pc, lds);
+    if (WAVES == kMixedWaves && (int)blockIdx.x < A.n_prefill) {
+        if constexpr (WAVES == kMixedWaves) {
+            const int32_t *pc = pieces + (int64_t)blockIdx.x * kItemInts;
+            prefill_item<D, E>(A, prefill + (int64_t)pc[PP_ITEM] * kItemInts, pc, lds);
+        }
     } else {
         const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-        const int idx = ((int)blockIdx.x - A.n_prefill) * kWgWaves + wave;
-        if (idx < A.n_decode) decode_item<D, E>(A, decode + (int64_t)idx * kItemInts);
+        const int idx = ((int)blockIdx.x - A.n_prefill) * WAVES + wave;
+        if (idx < A.n_decode) decode_item<D, E, (WAVES == kMixedWaves ? 4 : 2)>(A, decode + (int64_t)idx * kItemInts);
     }
 }
 
@@ -881,18 +1003,23 @@ int launch_kv_migrate(const tc_plan *p, bool import, int page0, int n_pages, int
 
 template <int D, class E>
 static int launch_attention_d(const tc_plan *p, const AttnArgs &A, hipStream_t st) {
-    static bool lds_ok = false;  // opt in to more than 64 KiB of dynamic LDS once per process
-    const int lds = PrefillCfg<D>::kLdsBytes;
-    if (!lds_ok) {
-        hipError_t e = hipFuncSetAttribute((const void *)mixed_attention_kernel<D, E>, hipFuncAttributeMaxDynamicSharedMemorySize, lds);
-        if (e != hipSuccess) return (int)e;
-        lds_ok = true;
-    }
     const int grid = p->grid_blocks();
     const AttnScalars sc = {A.n_prefill, A.n_decode, A.Hq, A.Hkv, A.G, A.scale_log2};
-    if (grid > 0)
-        mixed_attention_kernel<D, E><<<grid, kWgThreads, p->n_pieces > 0 ? lds : 0, st>>>(A.k_pool, A.v_pool, A.q, A.out, A.pages, A.prefill,
-                                                                                A.pieces, A.decode, A.ws_o, A.ws_ml, sc);
+    if (grid > 0 && p->n_pieces > 0) {
+        static bool lds_ok = false;  // opt in to more than 64 KiB of dynamic LDS once per process
+        const int lds = PrefillCfg<D>::kLdsBytes;
+        if (!lds_ok) {
+            hipError_t e = hipFuncSetAttribute((const void *)mixed_attention_kernel<D, E, kMixedWaves>,
+                                               hipFuncAttributeMaxDynamicSharedMemorySize, lds);
+            if (e != hipSuccess) return (int)e;
+            lds_ok = true;
+        }
+        mixed_attention_kernel<D, E, kMixedWaves><<<grid, kMixedWaves * 64, lds, st>>>(A.k_pool, A.v_pool, A.q, A.out, A.pages, A.prefill,
+                                                                                   A.pieces, A.decode, A.ws_o, A.ws_ml, sc);
+    } else if (grid > 0) {
+        mixed_attention_kernel<D, E, kDecodeWaves><<<grid, kDecodeWaves * 64, 0, st>>>(A.k_pool, A.v_pool, A.q, A.out, A.pages, A.prefill,
+                                                                                   A.pieces, A.decode, A.ws_o, A.ws_ml, sc);
+    }
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return (int)e;
     if (p->n_merge > 0)

@@ -31,7 +31,7 @@ tc_status check_pool_matches(const tc_plan *plan, const tc_kv_pool *pool, bool n
 // Decode KV ranges are cut into equal splits so that work items are uniform; the split
 // is the largest of 1024..128 tokens that still yields enough items to fill the chip.
 static int choose_split(int64_t decode_token_heads) {
-    const int64_t want_items = (int64_t)kNumCu * kWgPerCu * kWgWaves;  // one item per resident wavefront (finer splits measured slower)
+    const int64_t want_items = (int64_t)kNumCu * kDecodeWgPerCu * kDecodeWaves;  // one item per wavefront resident in a decode-only launch (finer splits measured slower)
     for (int split = kMaxSplitPages * kBlock; split > 128; split /= 2)
         if (decode_token_heads / split >= want_items) return split;
     return 128;
@@ -47,7 +47,7 @@ static int choose_split(int64_t decode_token_heads) {
 // slots are left alone (k = 1).
 template <class Tile>
 static void choose_prefill_cuts(Tile *tiles, size_t n, int Hkv, int64_t decode_bytes) {
-    const int64_t slots = (int64_t)kWgPerCu * kNumCu;
+    const int64_t slots = kNumCu;  // one prefill workgroup per compute unit
     const int64_t items = (int64_t)n * Hkv;
     if (items == 0 || items * 4 > slots) return;  // with more row blocks than that, cutting measured slower
     const int k_cap = (int)std::min<int64_t>(8, slots / items);
@@ -222,21 +222,6 @@ tc_status build_plan(const tc_kv_pool *pool, const tc_batch *b, tc_plan **out) {
                 }
         }
         std::stable_sort(pieces.begin(), pieces.end(), [](const Piece &x, const Piece &y) { return x.t1 - x.t0 > y.t1 - y.t0; });
-        // The first kWgPerCu * kNumCu workgroups are resident together, workgroup i on compute unit
-        // i mod kNumCu (observed dispatch order).  Handing every second round of kNumCu pieces out in
-        // reverse puts the heaviest piece of one round beside the lightest of the next, so the compute
-        // units finish together instead of in order of their load.  Groups of Hkv consecutive pieces (one
-        // per KV head) are kept intact so that workgroup id mod Hkv still names the KV head.
-        {
-            const size_t grp = (kNumCu % Hkv == 0) ? (size_t)Hkv : 1;
-            for (int r = 1; r < kWgPerCu; r += 2) {
-                const size_t lo = (size_t)r * kNumCu, hi = std::min(pieces.size(), lo + kNumCu);
-                if (lo >= hi) break;
-                const size_t n_grp = (hi - lo) / grp;  // whole groups only; a ragged rest stays in place
-                for (size_t a = 0, z = n_grp; a + 1 < z; a++, z--)
-                    std::swap_ranges(pieces.begin() + lo + a * grp, pieces.begin() + lo + (a + 1) * grp, pieces.begin() + lo + (z - 1) * grp);
-            }
-        }
         int32_t *pc = H + p->off_pieces;
         for (const Piece &x : pieces) {
             pc[PP_ITEM] = x.item; pc[PP_T0] = x.t0; pc[PP_T1] = x.t1; pc[PP_SLOT] = x.slot; pc[PP_K] = x.k;
@@ -306,7 +291,7 @@ tc_status tc_plan_get_info(const tc_plan *p, tc_plan_info *info) {
     info->num_prefill_items = p->n_prefill; info->num_decode_items = p->n_decode;
     info->num_merge_items = p->n_merge; info->num_partials = p->n_partials;
     info->split_tokens = p->split_tokens; info->rows_per_prefill_item = tc::kPrefillRows;
-    info->grid_blocks = p->grid_blocks(); info->block_threads = tc::kWgThreads;
+    info->grid_blocks = p->grid_blocks(); info->block_threads = p->wg_waves() * 64;
     info->total_pages = p->total_pages;
     info->num_prefill_pieces = p->n_pieces;
     return TC_OK;

@@ -174,16 +174,9 @@ def check_work_list(tc, sp, table, nb):
             for pos in range(int(item[3])):
                 slots += [base + pos * k + c for c in range(k)]
                 merge_expected.append((int(item[0]), int(item[1]), int(item[4] + item[2] + pos), base + pos * k, k))
-    # order: most tiles first, except that every second round of 256 resident workgroups (one per compute
-    # unit) runs lightest-first, so that heavy and light pieces meet on a compute unit
+    # order: most tiles first
     size = pc[:, 2] - pc[:, 1]
-    resident = 3 * 256
-    for r in range(0, min(len(size), resident), 256):
-        d = np.diff(size[r:r + 256])
-        assert np.all(d >= 0) if (r // 256) % 2 else np.all(d <= 0)
-    assert np.all(np.diff(size[resident:]) <= 0)
-    if len(size) > resident:
-        assert size[resident:].max() <= size[:resident].min()
+    assert np.all(np.diff(size) <= 0)
     if 256 % Hkv == 0:  # the KV head stays the fastest index: workgroup id mod Hkv names it
         assert np.all(pf[pc[:, 0], 1] == np.arange(len(pc)) % Hkv)
     # decode: splits tile [0, kv_len) page-aligned, <= 64 pages each
