@@ -438,6 +438,15 @@ struct PrefillWave {
     }
 };
 
+// The reference maximum of a row (log2 domain) is kept until the row's true maximum exceeds it by more
+// than this slack: probabilities then reach at most 2^kMaxSlack instead of 1, which fp32 sums and 16-bit
+// operands hold without loss of relative precision, and O has to be rescaled only a few times per sweep
+// instead of whenever any of a wave's 32 rows sees a new maximum.
+constexpr float kMaxSlack = 8.f;
+__device__ __forceinline__ float next_reference_max(float m_run, float row_max_log2) {
+    return row_max_log2 > m_run + kMaxSlack ? row_max_log2 : m_run;
+}
+
 // The KV sweep is software-pipelined inside every wave, in units of half a tile (32 tokens), three
 // halves deep: in one phase the matrix cores compute the scores of half h + 1 and accumulate P V of
 // half h - 1 while the vector ALU turns the scores of half h into probabilities.  (MFMA and VALU
@@ -524,7 +533,7 @@ __device__ void prefill_item(const AttnArgs &A, const int32_t *__restrict__ it, 
 #pragma unroll
         for (int e = 0; e < 8; e++) pb[b][e] = (el)0.f;
     if (t_begin * C::kTileTokens + 31 > wave_pmin) W::causal_mask(sc, t_begin * C::kTileTokens, hh, p_abs);
-    float m_new = fmaxf(m_run, W::row_max(sc) * c_log2);
+    float m_new = next_reference_max(m_run, W::row_max(sc) * c_log2);
     float alpha_o = 1.f;  // factor O still has to be multiplied with before the next P V product
 
     // One phase, for half-tile h: `cur` holds its scores S(h) (their maxima already in m_new), `kf` the K
@@ -546,7 +555,7 @@ __device__ void prefill_item(const AttnArgs &A, const int32_t *__restrict__ it, 
 #pragma unroll
                 for (int r = 0; r < 16; r++) o[c][r] *= alpha_o;
         }
-        alpha_o = fast_exp2(m_run - m_new);  // 1 unless this row's maximum moved
+        alpha_o = fast_exp2(m_run - m_new);  // 1 unless this row's reference maximum moved
         m_run = m_new;
         l_run *= alpha_o;
         if (QK) W::qk(kf, qreg, nxt);
@@ -555,7 +564,7 @@ __device__ void prefill_item(const AttnArgs &A, const int32_t *__restrict__ it, 
         W::load_v(v_h, hv, vf);
         W::probs(cur, c_log2, m_run, pb, l_run);
         if (MASK && QK) W::causal_mask(nxt, tok_nxt, hh, p_abs);
-        if (QK) m_new = fmaxf(m_run, W::row_max(nxt) * c_log2);
+        if (QK) m_new = next_reference_max(m_run, W::row_max(nxt) * c_log2);
         // the probabilities are used by the next phase: have them computed in this one
         asm volatile("" : "+v"(pb[0]), "+v"(pb[1]), "+v"(l_run), "+v"(m_new));
         if (!MASK && QK && KREAD) {
