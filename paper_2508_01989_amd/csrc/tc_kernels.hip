@@ -238,7 +238,7 @@ __global__ void __launch_bounds__(256) kv_migrate_kernel(const MigratePools pool
 }
 
 // ------------------------------------------------------------------------------------
-// Prefill branch: one workgroup = 128 (position, head) rows of one KV head, 32 per wave.
+// Prefill branch: one workgroup = 256 (position, head) rows of one KV head, 32 per wave.
 // ------------------------------------------------------------------------------------
 // Row R of the workgroup is position first_pos + R / G, query head kv_head * G + R % G.
 // The KV range 0..last position is swept in 64-token tiles (four pages); each tile is

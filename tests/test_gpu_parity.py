@@ -76,6 +76,13 @@ SMALL = {
     "five_kv_heads_d64": (5, 5, 64, [90, 1], [1200, 64]),
     "head_dim_64": (8, 8, 64, [64, 1, 1, 1, 1], [0, 36, 63, 99, 127]),
     "head_dim_64_gqa": (8, 2, 64, [200, 1, 1], [45, 1000, 17]),
+    # sweeps of one to four 64-token tiles (the copy pipeline runs three tiles ahead), ending on and off tile boundaries
+    "prefill_sweeps_of_one_to_four_tiles": (8, 2, 128, [64, 65, 2, 30, 129, 1], [0, 0, 126, 99, 127, 5]),
+    # row blocks of 256 rows that G does not divide (85 and 51 positions per block), several blocks per KV head
+    "row_blocks_g3_several": (6, 2, 128, [200, 1], [300, 40]),
+    "row_blocks_g5_several": (10, 2, 128, [110, 1], [77, 600]),
+    # a chunk of several row blocks whose waves leave the mask-free part of the sweep at different tiles
+    "several_row_blocks_mid_context": (32, 8, 128, [600, 1, 1], [1000, 2500, 31]),
     # few prefill row blocks over a long context: their KV ranges are cut into pieces that run as
     # separate workgroups and are merged (4, 3, 2 and 8 pieces)
     "cut_small_chunk_long_context": (32, 8, 128, [128, 1, 1], [2000, 100, 50]),
@@ -93,6 +100,26 @@ def test_small_cases_match_oracle(H, name):
     _, db = run_and_compare(H, b, name)
     cut = db.plan.info.num_prefill_pieces > db.plan.info.num_prefill_items
     assert cut or not name.startswith("cut_")
+
+
+def test_peaked_softmax_moves_the_reference_maximum(H):
+    """Queries 8x larger (an exact exponent shift of the seeded bf16 values): scores have a standard deviation of
+    about 11 in the log2 domain, so row maxima outgrow the kernel's slack of 8 again and again and the
+    rescaling of the running sums and of the accumulators is exercised throughout the sweep, in the
+    prefill branch (whole row block and cut pieces) and in the decode branch."""
+    for name, Hq, Hkv, q_len, ctx in (("peaked", 8, 2, [300, 1, 1], [500, 700, 40]), ("peaked_cut", 32, 8, [64, 1], [3000, 90])):
+        b = W.make_batch(W.custom_spec(name, Hq, Hkv, 128, q_len, ctx, seed=911))
+        q = b.q.copy()
+        finite_nonzero = ((q & 0x7F80) != 0) & ((q & 0x7F80) < (0xFF - 3) << 7)
+        q[finite_nonzero] += np.uint16(3 << 7)
+        b.q = q
+        # outputs are now close to single rows of V; halve V (exactly) so that the bf16 rounding of an output
+        # of magnitude up to 4.2 (half an ulp = 1/64 above 4) stays inside the absolute tolerance
+        for arr in ("v_new", "v_hist"):
+            v = getattr(b, arr).copy()
+            v[(v & 0x7F80) > (1 << 7)] -= np.uint16(1 << 7)
+            setattr(b, arr, v)
+        run_and_compare(H, b, name)
 
 
 # IEEE half, the precision the paper's own runs used (Sec. 4.1): 11 significant bits instead of 8, so
