@@ -674,10 +674,10 @@ __device__ void prefill_item(const AttnArgs &A, const int32_t *__restrict__ it, 
 //   S^T[token][head] = sum_d K[token][d] Q[head][d]   16x16x32, D/32 steps; lane gets tokens 4g..4g+3
 //   O^T[d][head]    += sum_token V^T[d][token] P^T[token][head]   16x16x16, contraction over the page's
 //                      16 tokens: lane feeds tokens 4g..4g+3
-// Pages resident in registers per wave (NS): one being consumed, the rest in flight.  A decode-only
-// launch runs twelve waves per compute unit and keeps two (168 VGPRs, three waves per SIMD; more measured
-// the same bandwidth); a mixed launch runs eight waves per compute unit with up to 256 registers each and
-// keeps four, so that its fewer waves have as many bytes in flight.
+// Pages resident in registers per wave: one being consumed, the rest in flight.  Two keep the
+// decode-only kernel within 168 VGPRs (three waves per SIMD); three or four measured the same
+// bandwidth, in the twelve-wave shape and in the eight-wave shape of a launch with a prefill chunk.
+constexpr int kDecodeStages = 2;
 
 template <int D>
 struct DecodePage {  // K and V of one page, in MFMA A-operand registers
@@ -746,13 +746,14 @@ __device__ __forceinline__ void decode_consume(const AttnArgs &A, DecodePage<D> 
     }
 }
 
-template <int D, class E, int NS>
+template <int D, class E>
 __device__ void decode_item(const AttnArgs &A, const int32_t *__restrict__ it) {
     using x8 = typename E::x8;
     using x4 = typename E::x4;
     using el = typename E::t;
     constexpr int KS = D / 32;  // k-steps of K Q^T
     constexpr int MT = D / 16;  // 16-row tiles of O^T
+    constexpr int NS = kDecodeStages;
     const int lane = threadIdx.x & 63;
     const int j = lane & 15, g = lane >> 4;
     const int kvh = it[DC_KVH], t0 = it[DC_BEGIN], t1 = it[DC_END], qrow = it[DC_QROW], slot = it[DC_SLOT];
@@ -850,7 +851,7 @@ __global__ void __launch_bounds__(WAVES * 64, WAVES == kMixedWaves ? 1 : kDecode
     } else {
         const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
         const int idx = ((int)blockIdx.x - A.n_prefill) * WAVES + wave;
-        if (idx < A.n_decode) decode_item<D, E, (WAVES == kMixedWaves ? 4 : 2)>(A, decode + (int64_t)idx * kItemInts);
+        if (idx < A.n_decode) decode_item<D, E>(A, decode + (int64_t)idx * kItemInts);
     }
 }
 
