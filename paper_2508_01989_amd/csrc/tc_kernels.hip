@@ -28,6 +28,10 @@
 
 #include "tc_internal.h"
 
+#ifndef TC_PREFILL_STAGES
+#define TC_PREFILL_STAGES 3
+#endif
+
 namespace tc {
 
 typedef float f32x4_t __attribute__((ext_vector_type(4)));
@@ -254,10 +258,12 @@ struct PrefillCfg {
     static constexpr int kPageBytes = kBlock * D * 2;               // one (page, KV head) tile of K or of V
     static constexpr int kTileBytes = kTilePages * kPageBytes;      // K part or V part of one LDS stage
     static constexpr int kRuns = kPageBytes / 1024;                 // 1 KiB wave-wide loads per page and tensor
-    // Three LDS stages of K and three of V: a tile is copied two steps before its first use, so the
-    // copies have two whole steps to land.  96 KiB at D = 128.
-    static constexpr int kStages = 3;
-    static constexpr int kLdsBytes = 2 * kStages * kTileBytes;
+    // kStages LDS stages of K and of V: a tile is copied kStages - 1 steps before its first use.
+    // 96 KiB at D = 128 with three stages, 128 KiB with four.
+    static constexpr int kStages = TC_PREFILL_STAGES;
+    static_assert(kStages == 3 || kStages == 4, "the page-id pipeline below is written for 3 or 4 stages");
+    static constexpr int kIdSlots = kStages - 2;  // page ids in flight per wave
+    static constexpr int kLdsBytes = 2 * kStages * kTileBytes + kMixedWaves * kIdSlots * 64 * 4;
 };
 
 // N direct-to-LDS loads of 1 KiB each (16 bytes per lane) at immediate offsets 0, 1024, ...
@@ -344,19 +350,18 @@ __device__ __forceinline__ void prefill_fix_tail(char *lds_v, int tile, int wave
 
 __device__ __forceinline__ void wait_all_loads() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); }
 
-// A page id fetched with a vector load, so that it is counted by vmcnt like the tile copies and the
-// LDS operand reads keep exact lgkmcnt waits (a scalar load in flight would force them to wait for
-// everything).  page_id_issue starts the load; the value may be used only after page_id_wait, which
-// also waits for every tile copy issued before the page id load (loads return in order).
-__device__ __forceinline__ int page_id_issue(const int32_t *p) {
-    int v;
-    asm volatile("global_load_dword %0, %1, off" : "=v"(v) : "v"(p) : "memory");
-    return v;
+// The page id of a wave's future tile copy is fetched with a direct-to-LDS load into a slot of the
+// wave's own (every lane loads the same id and deposits it at slot + 4 * lane): it is counted by
+// vmcnt like the tile copies (a scalar load in flight would force the LDS operand reads to wait
+// for everything), and no register is ever pending: the value is read from LDS after the wait.
+constexpr int kIdSlotBytes = 64 * 4;
+__device__ __forceinline__ void page_id_fetch(const int32_t *p, char *slot) {
+    __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)p, (__attribute__((address_space(3))) void *)slot, 4, 0, 0);
 }
-template <int N>  // N = loads issued after the page id load that may stay in flight
-__device__ __forceinline__ int page_id_wait(int v) {
-    asm volatile("s_waitcnt vmcnt(%1)" : "+v"(v) : "n"(N) : "memory");
-    return __builtin_amdgcn_readfirstlane(v);
+template <int N>  // wait until at most the N most recent loads of this wave are in flight
+__device__ __forceinline__ void wait_loads_but() { asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory"); }
+__device__ __forceinline__ int page_id_read(const char *slot, int lane) {
+    return __builtin_amdgcn_readfirstlane(*reinterpret_cast<const int *>(slot + 4 * lane));
 }
 
 // max / sum across the two half-waves (lanes l and l ^ 32 hold the two halves of a row).
@@ -504,19 +509,27 @@ __device__ void prefill_item(const AttnArgs &A, const int32_t *__restrict__ it, 
     float m_run = -1e30f;  // running row maximum (log2 domain)
     float l_run = 0.f;     // running sum of this lane's half of the row
 
-    // ---- prologue: tile j of the sweep lives in stage j mod 3 of its tensor.  K(0..2) and V(0..1) are
-    // copied here; step j then copies K(j+3) and V(j+2).  `ahead` = how far this wave's copy of a step
-    // runs ahead of the step's own tile.
+    // ---- prologue: tile j of the sweep lives in stage j mod NS of its tensor.  K(0..NS-1) and V(0..NS-2)
+    // are copied here; step j then copies K(j+NS) and V(j+NS-1).  `ahead` = how far this wave's copy of a
+    // step runs ahead of the step's own tile.
+    constexpr int NS = C::kStages;
     const TileCopier<D> cp(A, kvh, lds_k, lds_v, wave, lane);
-    const int ahead = cp.is_v ? 2 : 3;
-    cp.copy(prefill_page_id<D>(pages, n_pages, t_begin, cp.page_in_tile), 0);
-    cp.copy(prefill_page_id<D>(pages, n_pages, t_begin + 1, cp.page_in_tile), 1);
-    if (!cp.is_v) cp.copy(prefill_page_id<D>(pages, n_pages, t_begin + 2, cp.page_in_tile), 2);
+    const int ahead = cp.is_v ? NS - 1 : NS;
+#pragma unroll
+    for (int t = 0; t < NS - 1; t++) cp.copy(prefill_page_id<D>(pages, n_pages, t_begin + t, cp.page_in_tile), t);
+    if (!cp.is_v) cp.copy(prefill_page_id<D>(pages, n_pages, t_begin + NS - 1, cp.page_in_tile), NS - 1);
     int id_cur = prefill_page_id<D>(pages, n_pages, t_begin + ahead, cp.page_in_tile);  // page this wave copies in step 0
+    // The page id for the copy of step j is fetched in step j - (NS - 2) into slot j mod (NS - 2) of this
+    // wave; those of steps 1 .. NS - 3 are fetched here.
+    char *const id_slots = lds + 2 * NS * C::kTileBytes + wave * (C::kIdSlots * kIdSlotBytes);
+#pragma unroll
+    for (int t = 1; t < C::kIdSlots; t++)
+        page_id_fetch(pages + min((t_begin + t + ahead) * C::kTilePages + cp.page_in_tile, n_pages - 1), id_slots + t * kIdSlotBytes);
     wait_all_loads();
     if (cp.is_v) {
-        if ((t_begin + 1) * C::kTileTokens > kv_len) prefill_fix_tail<D>(lds_v, t_begin, cp.page_in_tile, lane, kv_len);
-        if ((t_begin + 2) * C::kTileTokens > kv_len) prefill_fix_tail<D>(lds_v + C::kTileBytes, t_begin + 1, cp.page_in_tile, lane, kv_len);
+#pragma unroll
+        for (int t = 0; t < NS - 1; t++)
+            if ((t_begin + t + 1) * C::kTileTokens > kv_len) prefill_fix_tail<D>(lds_v + t * C::kTileBytes, t_begin + t, cp.page_in_tile, lane, kv_len);
     }
     __syncthreads();
     x8 kf[KS];     // K fragments of the half whose scores are computed next
@@ -586,32 +599,35 @@ __device__ void prefill_item(const AttnArgs &A, const int32_t *__restrict__ it, 
             }
         }
     };
-    // One step for tile t_begin + j, which lives in stage s0 = j mod 3: `sc` holds the scores of its first
+    // One step for tile t_begin + j, which lives in stage s0 = j mod NS: `sc` holds the scores of its first
     // half, `kf` the K fragments of its second half.  NEXT: tile j + 1 exists.
-    int s0 = 0;
+    int s0 = 0, id_slot = 0;  // stage of the step's tile; slot that receives the page id fetched in the step (j mod (NS - 2))
     auto step = [&](int j, auto mask_tag, auto next_tag) {
         constexpr bool NEXT = decltype(next_tag)::value;
         const int tile = t_begin + j;
-        const int s1 = s0 == C::kStages - 1 ? 0 : s0 + 1, s2 = s1 == C::kStages - 1 ? 0 : s1 + 1;
+        const int s1 = s0 == NS - 1 ? 0 : s0 + 1, sm1 = s0 == 0 ? NS - 1 : s0 - 1;
         lds_cptr k_nxt = (lds_cptr)(lds_k + s1 * C::kTileBytes + k_lane_off);
         lds_cptr v_cur = (lds_cptr)(lds_v + s0 * C::kTileBytes + v_lane_off);
         // have both operand addresses in registers here, outside the scheduled regions below
         asm volatile("" : "+v"(k_nxt), "+v"(v_cur));
-        __syncthreads();  // every wave is done with step j - 1; the copies issued in step j - 2 are visible
-        int id_nxt = 0;
+        __syncthreads();  // every wave is done with step j - 1; the copies issued in step j - (NS - 1) are visible
         if (NEXT) {
-            // first the page id for the next step's copy, then this step's copy: K(j+3) replaces K(j),
-            // V(j+2) replaces V(j-1).  Past the end of the range the page index is clamped and the copy
+            // first the page id for the copy of step j + NS - 2, then this step's copy: K(j+NS) replaces K(j),
+            // V(j+NS-1) replaces V(j-1).  Past the end of the range the page index is clamped and the copy
             // is never read.
-            id_nxt = page_id_issue(pages + min((tile + 1 + ahead) * C::kTilePages + cp.page_in_tile, n_pages - 1));
-            cp.copy(id_cur, cp.is_v ? s2 : s0);
+            page_id_fetch(pages + min((tile + NS - 2 + ahead) * C::kTilePages + cp.page_in_tile, n_pages - 1),
+                          id_slots + id_slot * kIdSlotBytes);
+            cp.copy(id_cur, cp.is_v ? sm1 : s0);
         }
         const std::true_type yes;
         phase(v_cur, 0, k_nxt, 0, sc, sn, tile * C::kTileTokens + 32, mask_tag, yes, next_tag);
         phase(v_cur, 1, k_nxt, 1, sn, sc, (tile + 1) * C::kTileTokens, mask_tag, next_tag, next_tag);
         if (NEXT) {
-            // everything but this step's copy has landed: the next page id and the copies of step j - 1
-            id_cur = page_id_wait<C::kRuns>(id_nxt);
+            // loads return in order: all but the copies of the last NS - 2 steps and the page ids fetched
+            // after the one for step j + 1 have landed, i.e. that page id and the copies of step j - (NS - 2)
+            wait_loads_but<(NS - 2) * (C::kRuns + 1) - 1>();
+            id_slot = id_slot == C::kIdSlots - 1 ? 0 : id_slot + 1;  // slot of step j + 1
+            id_cur = page_id_read(id_slots + id_slot * kIdSlotBytes, lane);
             if (decltype(mask_tag)::value && cp.is_v && (tile + 2) * C::kTileTokens > kv_len)
                 prefill_fix_tail<D>(lds_v + s1 * C::kTileBytes, tile + 1, cp.page_in_tile, lane, kv_len);
         }
