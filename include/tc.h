@@ -142,6 +142,17 @@ tc_status tc_kv_append(const tc_plan *plan, const tc_kv_pool *pool, const void *
 tc_status tc_mixed_attention(const tc_plan *plan, const tc_kv_pool *pool, const void *q, void *out, float scale,
                              void *workspace, size_t workspace_bytes, void *stream);
 
+/* The two launches of tc_mixed_attention, one per call, for callers that time them or put other
+ * work between them (same operation, paper Sec. 2.1; same arguments, checks and errors).
+ * tc_attention_partials runs the attention kernel: rows whose KV range is not split are final in
+ * `out`, the others leave fp32 partial results in the workspace.  tc_split_merge combines those
+ * partials into `out`; it launches nothing when the plan has no split range.  The pair, in this
+ * order on one stream with the same out and workspace, is bit for bit tc_mixed_attention. */
+tc_status tc_attention_partials(const tc_plan *plan, const tc_kv_pool *pool, const void *q, void *out, float scale,
+                                void *workspace, size_t workspace_bytes, void *stream);
+tc_status tc_split_merge(const tc_plan *plan, const tc_kv_pool *pool, void *out, void *workspace,
+                         size_t workspace_bytes, void *stream);
+
 /* Test hook: un-paged copy of tokens 0..ctx+q_len-1 of sequence `seq` out of the pool,
  * k_out / v_out DEVICE [kv_len][Hkv][D] bf16. */
 tc_status tc_kv_gather(const tc_plan *plan, const tc_kv_pool *pool, int32_t seq, void *k_out, void *v_out,

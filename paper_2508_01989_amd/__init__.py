@@ -17,7 +17,8 @@ TC_OK, TC_ERR_NULL, TC_ERR_SHAPE, TC_ERR_SPAN, TC_ERR_BLOCK, TC_ERR_WORKSPACE, T
 TC_BF16, TC_FP16 = 1, 2
 
 EXPORTS = ["tc_plan_create", "tc_plan_create_host", "tc_plan_get_info", "tc_plan_copy_items",
-           "tc_plan_workspace_bytes", "tc_plan_destroy", "tc_kv_append", "tc_mixed_attention", "tc_kv_gather",
+           "tc_plan_workspace_bytes", "tc_plan_destroy", "tc_kv_append", "tc_mixed_attention", "tc_attention_partials", "tc_split_merge",
+           "tc_kv_gather",
            "tc_kv_transfer_bytes", "tc_kv_export", "tc_kv_import", "tc_status_str", "tc_last_error", "tc_version"]
 
 
@@ -67,6 +68,8 @@ def lib():
         L.tc_plan_destroy.restype = None
         L.tc_kv_append.argtypes = [vp, C.POINTER(tc_kv_pool), vp, vp, vp]
         L.tc_mixed_attention.argtypes = [vp, C.POINTER(tc_kv_pool), vp, vp, C.c_float, vp, C.c_size_t, vp]
+        L.tc_attention_partials.argtypes = L.tc_mixed_attention.argtypes
+        L.tc_split_merge.argtypes = [vp, C.POINTER(tc_kv_pool), vp, vp, C.c_size_t, vp]
         L.tc_kv_gather.argtypes = [vp, C.POINTER(tc_kv_pool), C.c_int32, vp, vp, vp]
         L.tc_kv_transfer_bytes.argtypes = [vp, C.c_int32, C.c_int32]
         L.tc_kv_transfer_bytes.restype = C.c_size_t
@@ -169,6 +172,19 @@ def tc_mixed_attention(plan: Plan, pool: tc_kv_pool, q, out, scale, workspace=No
         workspace_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
     _check(lib().tc_mixed_attention(plan.handle, C.byref(pool), _ptr(q), _ptr(out), C.c_float(scale), _ptr(workspace),
                                     workspace_bytes, _stream(stream)))
+
+
+def tc_attention_partials(plan: Plan, pool: tc_kv_pool, q, out, scale, workspace=None, workspace_bytes=None, stream=None):
+    if workspace_bytes is None:
+        workspace_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    _check(lib().tc_attention_partials(plan.handle, C.byref(pool), _ptr(q), _ptr(out), C.c_float(scale), _ptr(workspace),
+                                       workspace_bytes, _stream(stream)))
+
+
+def tc_split_merge(plan: Plan, pool: tc_kv_pool, out, workspace=None, workspace_bytes=None, stream=None):
+    if workspace_bytes is None:
+        workspace_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    _check(lib().tc_split_merge(plan.handle, C.byref(pool), _ptr(out), _ptr(workspace), workspace_bytes, _stream(stream)))
 
 
 def tc_kv_gather(plan: Plan, pool: tc_kv_pool, seq, k_out, v_out, stream=None):

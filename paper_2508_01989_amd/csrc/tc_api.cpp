@@ -22,6 +22,18 @@ tc_status check_runnable(const tc_plan *plan, const tc_kv_pool *pool) {
     return TC_OK;
 }
 
+tc_status attention(const tc_plan *plan, const tc_kv_pool *pool, const void *q, void *out, float scale, void *workspace,
+                    size_t workspace_bytes, int launches, void *stream, const char *what) {
+    tc_status st = check_runnable(plan, pool);
+    if (st != TC_OK) return st;
+    if (plan->T == 0) return TC_OK;
+    if (!out || (!q && (launches & tc::kLaunchAttention))) return fail(TC_ERR_NULL, "q or out is NULL");
+    const size_t need = plan->workspace_bytes();
+    if (need > 0 && (!workspace || workspace_bytes < need)) return fail(TC_ERR_WORKSPACE, "workspace missing or too small");
+    if (!(scale > 0.f) || scale > 3.0e38f) return fail(TC_ERR_ARG, "scale must be positive and finite");
+    return device_result(tc::launch_attention(plan, pool, q, out, scale, need ? workspace : nullptr, launches, stream), what);
+}
+
 }  // namespace
 
 extern "C" {
@@ -36,15 +48,19 @@ tc_status tc_kv_append(const tc_plan *plan, const tc_kv_pool *pool, const void *
 
 tc_status tc_mixed_attention(const tc_plan *plan, const tc_kv_pool *pool, const void *q, void *out, float scale,
                              void *workspace, size_t workspace_bytes, void *stream) {
-    tc_status st = check_runnable(plan, pool);
-    if (st != TC_OK) return st;
-    if (plan->T == 0) return TC_OK;
-    if (!q || !out) return fail(TC_ERR_NULL, "q or out is NULL");
-    const size_t need = plan->workspace_bytes();
-    if (need > 0 && (!workspace || workspace_bytes < need)) return fail(TC_ERR_WORKSPACE, "workspace missing or too small");
-    if (!(scale > 0.f) || scale > 3.0e38f) return fail(TC_ERR_ARG, "scale must be positive and finite");
-    return device_result(tc::launch_attention(plan, pool, q, out, scale, need ? workspace : nullptr, stream),
-                         "tc_mixed_attention launch");
+    return attention(plan, pool, q, out, scale, workspace, workspace_bytes, tc::kLaunchAttention | tc::kLaunchMerge, stream,
+                     "tc_mixed_attention launch");
+}
+
+tc_status tc_attention_partials(const tc_plan *plan, const tc_kv_pool *pool, const void *q, void *out, float scale,
+                                void *workspace, size_t workspace_bytes, void *stream) {
+    return attention(plan, pool, q, out, scale, workspace, workspace_bytes, tc::kLaunchAttention, stream,
+                     "tc_attention_partials launch");
+}
+
+tc_status tc_split_merge(const tc_plan *plan, const tc_kv_pool *pool, void *out, void *workspace, size_t workspace_bytes,
+                         void *stream) {
+    return attention(plan, pool, nullptr, out, 1.f, workspace, workspace_bytes, tc::kLaunchMerge, stream, "tc_split_merge launch");
 }
 
 tc_status tc_kv_gather(const tc_plan *plan, const tc_kv_pool *pool, int32_t seq, void *k_out, void *v_out, void *stream) {

@@ -75,8 +75,10 @@ tc_status check_pool_matches(const tc_plan *plan, const tc_kv_pool *pool, bool n
 // Kernel launchers (tc_kernels.hip).  All return hipError_t as int (0 = success).
 int launch_kv_append(const tc_plan *p, const tc_kv_pool *pool, const void *k_new, const void *v_new, void *stream);
 int launch_kv_gather(const tc_plan *p, const tc_kv_pool *pool, int seq, void *k_out, void *v_out, void *stream);
+// `launches`: which of the two launches to make (the attention kernel, the merge of split KV ranges).
+constexpr int kLaunchAttention = 1, kLaunchMerge = 2;
 int launch_attention(const tc_plan *p, const tc_kv_pool *pool, const void *q, void *out, float scale,
-                     void *workspace, void *stream);
+                     void *workspace, int launches, void *stream);
 // Pool <-> transfer buffer copy of the pages [page0, page0 + n_pages) of the plan, all layers.
 int launch_kv_migrate(const tc_plan *p, bool import, int page0, int n_pages, int num_layers, void *const *k_pools,
                       void *const *v_pools, void *buffer, void *stream);

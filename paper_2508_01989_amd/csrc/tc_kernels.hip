@@ -1028,8 +1028,8 @@ int launch_kv_migrate(const tc_plan *p, bool import, int page0, int n_pages, int
 }
 
 template <int D, class E>
-static int launch_attention_d(const tc_plan *p, const AttnArgs &A, hipStream_t st) {
-    const int grid = p->grid_blocks();
+static int launch_attention_d(const tc_plan *p, const AttnArgs &A, int launches, hipStream_t st) {
+    const int grid = (launches & kLaunchAttention) ? p->grid_blocks() : 0;
     const AttnScalars sc = {A.n_prefill, A.n_decode, A.Hq, A.Hkv, A.G, A.scale_log2};
     if (grid > 0 && p->n_pieces > 0) {
         static bool lds_ok = false;  // opt in to more than 64 KiB of dynamic LDS once per process
@@ -1048,13 +1048,13 @@ static int launch_attention_d(const tc_plan *p, const AttnArgs &A, hipStream_t s
     }
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return (int)e;
-    if (p->n_merge > 0)
+    if ((launches & kLaunchMerge) && p->n_merge > 0)
         split_merge_kernel<D, E><<<p->n_merge, 256, 0, st>>>(p->dev + p->off_merge, A.ws_o, A.ws_ml, A.out, A.Hq, A.G);
     return (int)hipGetLastError();
 }
 
 int launch_attention(const tc_plan *p, const tc_kv_pool *pool, const void *q, void *out, float scale, void *workspace,
-                     void *stream) {
+                     int launches, void *stream) {
     AttnArgs A;
     A.k_pool = (const uint16_t *)pool->k_pool;
     A.v_pool = (const uint16_t *)pool->v_pool;
@@ -1073,8 +1073,8 @@ int launch_attention(const tc_plan *p, const tc_kv_pool *pool, const void *q, vo
     A.G = p->G;
     A.scale_log2 = scale * 1.4426950408889634f;
     hipStream_t st = (hipStream_t)stream;
-    if (p->dtype == TC_FP16) return p->D == 128 ? launch_attention_d<128, Fp16>(p, A, st) : launch_attention_d<64, Fp16>(p, A, st);
-    return p->D == 128 ? launch_attention_d<128, Bf16>(p, A, st) : launch_attention_d<64, Bf16>(p, A, st);
+    if (p->dtype == TC_FP16) return p->D == 128 ? launch_attention_d<128, Fp16>(p, A, launches, st) : launch_attention_d<64, Fp16>(p, A, launches, st);
+    return p->D == 128 ? launch_attention_d<128, Bf16>(p, A, launches, st) : launch_attention_d<64, Bf16>(p, A, launches, st);
 }
 
 }  // namespace tc

@@ -7,7 +7,8 @@ from __future__ import annotations
 import numpy as np
 import torch
 
-from . import TC_BF16, TC_FP16, Plan, make_pool, tc_kv_append, tc_kv_gather, tc_mixed_attention
+from . import (TC_BF16, TC_FP16, Plan, make_pool, tc_attention_partials, tc_kv_append, tc_kv_gather, tc_mixed_attention,
+               tc_split_merge)
 
 
 def to_dev(a: np.ndarray, device="cuda:0") -> torch.Tensor:
@@ -64,6 +65,15 @@ class DeviceBatch:
     def attention(self):
         tc_mixed_attention(self.plan, self.pool, self.q, self.out, self.spec.scale, self.workspace,
                            self.plan.workspace_bytes, stream=self.stream)
+
+    def attention_partials(self):
+        """First launch of attention(): the attention kernel alone."""
+        tc_attention_partials(self.plan, self.pool, self.q, self.out, self.spec.scale, self.workspace,
+                              self.plan.workspace_bytes, stream=self.stream)
+
+    def split_merge(self):
+        """Second launch of attention(): the merge of split KV ranges."""
+        tc_split_merge(self.plan, self.pool, self.out, self.workspace, self.plan.workspace_bytes, stream=self.stream)
 
     def step(self):
         """One pass of the hot path for one layer: KV append, then mixed-batch attention."""

@@ -205,6 +205,38 @@ def test_bitwise_reproducible_and_independent_of_poison(H):
     assert np.array_equal(H.to_host(db2.out), first)
 
 
+def test_two_launch_form_equals_the_single_call(H):
+    """tc_attention_partials then tc_split_merge is bit for bit tc_mixed_attention: on a batch with split
+    decode ranges and a cut prefill chunk, on one without any split (merge launches nothing), and
+    the merge alone must leave rows of unsplit sequences untouched."""
+    import paper_2508_01989_amd as tc
+    import torch
+    for name, q_len, ctx in [("split", [300, 1, 1, 1], [100, 2000, 50, 700]), ("nosplit", [40, 1, 1], [0, 30, 90])]:
+        b = W.make_batch(W.custom_spec("two_" + name, 32, 8, 128, q_len, ctx, seed=78))
+        db = H.DeviceBatch(b)
+        assert (db.plan.workspace_bytes > 0) == (name == "split")
+        db.step()
+        single = H.to_host(db.out).copy()
+        db.out.fill_(0)
+        db.attention_partials()
+        torch.cuda.synchronize()
+        after_first = H.to_host(db.out).copy()
+        db.split_merge()
+        torch.cuda.synchronize()
+        both = H.to_host(db.out)
+        assert np.array_equal(both, single), name
+        if name == "nosplit":
+            assert np.array_equal(after_first, single)
+        else:
+            assert not np.array_equal(after_first, single)
+            # the merge writes only rows the first launch left at the fill value
+            written = np.any(after_first != 0, axis=(1, 2))
+            assert np.array_equal(both[written], after_first[written])
+    with pytest.raises(tc.TcError) as e:
+        tc.tc_split_merge(db.plan, db.pool, None, db.workspace, db.plan.workspace_bytes)
+    assert e.value.status == tc.TC_ERR_NULL
+
+
 def test_block_table_relabelling_is_bitwise_invisible(H):
     b = W.make_batch(W.custom_spec("perm", 8, 2, 128, [100, 1, 1], [60, 300, 31], seed=5))
     db = H.DeviceBatch(b)
