@@ -102,6 +102,34 @@ def test_small_cases_match_oracle(H, name):
     assert cut or not name.startswith("cut_")
 
 
+def random_mix(seed):
+    """A seeded random batch shape: head layout, one to three prefill segments and up to eight decodes of
+    mixed lengths (short ones, ones around page, tile and split boundaries, long ones), in random order."""
+    rng = np.random.default_rng(seed)
+    D = int(rng.choice([64, 128]))
+    G = int(rng.choice([1, 2, 3, 4, 8]))
+    Hkv = int(rng.integers(1, 5))
+    edge = [0, 1, 15, 16, 17, 63, 64, 65, 127, 128, 129, 255, 256, 257, 1023, 1024, 1025]
+    q_len, ctx = [], []
+    for _ in range(int(rng.integers(1, 4))):
+        q_len.append(int(rng.choice([2, 3, 31, 64, 65, int(rng.integers(2, 400))])))
+        ctx.append(int(rng.choice([0, int(rng.choice(edge)), int(rng.integers(0, 2500))])))
+    for _ in range(int(rng.integers(0, 9))):
+        q_len.append(1)
+        ctx.append(int(rng.choice([int(rng.choice(edge)), int(rng.integers(0, 300)), int(rng.integers(0, 6000))])))
+    order = rng.permutation(len(q_len))
+    return G * Hkv, Hkv, D, [q_len[i] for i in order], [ctx[i] for i in order]
+
+
+@pytest.mark.parametrize("seed", range(24))
+def test_random_mixes_match_oracle(H, seed):
+    Hq, Hkv, D, q_len, ctx = random_mix(1000 + seed)
+    print(f"[mix {seed}] Hq={Hq} Hkv={Hkv} D={D} q_len={q_len} ctx={ctx}", flush=True)
+    b = W.make_batch(W.custom_spec(f"mix{seed}", Hq, Hkv, D, q_len, ctx, seed=4000 + seed,
+                                   dtype="fp16" if seed % 4 == 3 else "bf16"))
+    run_and_compare(H, b, f"mix{seed}")
+
+
 def test_peaked_softmax_moves_the_reference_maximum(H):
     """Queries 8x larger (an exact exponent shift of the seeded bf16 values): scores have a standard deviation of
     about 11 in the log2 domain, so row maxima outgrow the kernel's slack of 8 again and again and the
