@@ -87,10 +87,11 @@ typedef struct {
     int32_t num_seqs, total_q;          /* S, T                                              */
     int32_t num_prefill_seqs, num_decode_seqs;
     int32_t num_prefill_items;          /* row blocks of the prefill branch                  */
-    int32_t num_decode_items;           /* wave-sized KV splits of the decode branch         */
+    int32_t num_decode_items;           /* wave slots of the decode branch: one KV split each, */
+                                        /* padding included (whole workgroups)               */
     int32_t num_merge_items;            /* (query row, KV head) pairs that need the merge    */
-    int32_t num_partials;               /* split partials held in the workspace              */
-    int32_t split_tokens;               /* KV tokens per decode split                        */
+    int32_t num_partials;               /* partial results held in the workspace             */
+    int32_t split_tokens;               /* most KV tokens a decode split holds               */
     int32_t rows_per_prefill_item;      /* (position, head) rows per prefill workgroup       */
     int32_t grid_blocks, block_threads; /* launch shape of the fused attention kernel        */
     int64_t total_pages;                /* table entries copied                              */
@@ -112,12 +113,18 @@ tc_status tc_plan_get_info(const tc_plan *plan, tc_plan_info *info);
 /* Copy work items to HOST memory for inspection: kind 0 = prefill items, 1 = decode, 2 = merge,
  * 3 = prefill pieces; 8 int32 per item, at most cap_items items.  Fields:
  *   prefill {seq, kv_head, first_local_pos, num_pos, q_row0, ctx, page_off, num_pages}
- *   decode  {seq, kv_head, kv_begin, kv_end, q_row, partial_slot (-1 = writes out), page_off, 0}
- *   merge   {seq, kv_head, q_row, first_partial_slot, num_splits, 0, 0, 0}
+ *   decode  {seq, kv_head, kv_begin, kv_end, q_row, partial_slot (-1 = writes out), page_off,
+ *            team members | position in team << 8}
+ *   merge   {seq, kv_head, q_row, first_partial_slot, num_partials, 0, 0, 0}
  *   piece   {prefill item, first 64-token KV tile, end tile, partial slot of the item's first position
  *            (-1 = the piece is the whole item and writes out), pieces of the item, 0, 0, 0}
  * A batch with few prefill row blocks has their KV ranges cut into pieces that run as separate
- * workgroups; position i of such an item owns partial slots slot + i * pieces .. + pieces - 1. */
+ * workgroups; position i of such an item owns partial slots slot + i * pieces .. + pieces - 1.
+ * Decode items come in workgroups of block_threads / 64 wave slots.  The splits of a sequence hold the
+ * same number of pages up to one.  Consecutive splits of one (sequence, KV head) in one workgroup are a
+ * team (consecutive items, positions 0..members-1, all carrying the team's partial_slot): the workgroup
+ * combines their results, and the team writes the output rows (-1) or one partial result.  An item
+ * with kv_begin = kv_end (seq = -1) is padding at the end of the list. */
 tc_status tc_plan_copy_items(const tc_plan *plan, int32_t kind, int32_t *dst, size_t cap_items);
 
 /* Bytes of DEVICE scratch tc_mixed_attention needs for this plan (may be 0). */

@@ -29,7 +29,7 @@ constexpr int kMaxLayers = 4096;
 
 // Field indices of work items (see tc_plan_copy_items in tc.h).
 enum { PF_SEQ, PF_KVH, PF_POS0, PF_NPOS, PF_QROW0, PF_CTX, PF_PAGEOFF, PF_NPAGES };
-enum { DC_SEQ, DC_KVH, DC_BEGIN, DC_END, DC_QROW, DC_SLOT, DC_PAGEOFF, DC_PAD };
+enum { DC_SEQ, DC_KVH, DC_BEGIN, DC_END, DC_QROW, DC_SLOT, DC_PAGEOFF, DC_TEAM };  // DC_TEAM: members | position << 8
 enum { MG_SEQ, MG_KVH, MG_QROW, MG_SLOT0, MG_NSPLIT };
 // A prefill piece is what one workgroup runs: KV tiles [T0, T1) of a prefill item.  SLOT is -1 when
 // the piece is the whole item (it writes the output rows); otherwise position i of the item writes

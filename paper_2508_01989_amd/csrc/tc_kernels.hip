@@ -763,8 +763,14 @@ __device__ __forceinline__ void decode_consume(const AttnArgs &A, DecodePage<D> 
     }
 }
 
+// The splits of one (sequence, KV head) that share a workgroup form a team (consecutive waves): the
+// members leave their (m, l, O) in LDS and the team's first wave combines them, in wave order, with its
+// own and writes the output rows, or one partial result if the (sequence, KV head) has more teams.
+// Bytes of LDS a decode workgroup of `waves` waves needs for that.
+__host__ __device__ constexpr size_t decode_team_lds_bytes(int waves, int G, int D) { return (size_t)waves * G * (D + 2) * sizeof(float); }
+
 template <int D, class E>
-__device__ void decode_item(const AttnArgs &A, const int32_t *__restrict__ it) {
+__device__ void decode_item(const AttnArgs &A, const int32_t *__restrict__ it, float *team_lds, int wg_waves) {
     using x8 = typename E::x8;
     using x4 = typename E::x4;
     using el = typename E::t;
@@ -772,62 +778,92 @@ __device__ void decode_item(const AttnArgs &A, const int32_t *__restrict__ it) {
     constexpr int MT = D / 16;  // 16-row tiles of O^T
     constexpr int NS = kDecodeStages;
     const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int j = lane & 15, g = lane >> 4;
     const int kvh = it[DC_KVH], t0 = it[DC_BEGIN], t1 = it[DC_END], qrow = it[DC_QROW], slot = it[DC_SLOT];
+    const int team_n = it[DC_TEAM] & 0xff, team_pos = it[DC_TEAM] >> 8;
     const int G = A.G;
-    const int page0 = t0 / kBlock;
-    const int n_tok = t1 - t0;
-    const int n_pg = (n_tok + kBlock - 1) / kBlock;  // 1..64
-    const int32_t *pages = A.pages + it[DC_PAGEOFF] + page0;
-    const int my_page = pages[min(lane, n_pg - 1)];  // lane i holds the id of page i of the split
-
-    x8 qreg[KS];
-    const int64_t q_off = ((int64_t)qrow * A.Hq + kvh * G + min(j, G - 1)) * D;
-#pragma unroll
-    for (int kk = 0; kk < KS; kk++) {
-        u32x4 w = *reinterpret_cast<const u32x4 *>(A.q + q_off + (4 * kk + g) * 8);
-        if (j >= G) w = u32x4{0u, 0u, 0u, 0u};
-        qreg[kk] = __builtin_bit_cast(x8, w);
-    }
+    const int n_tok = t1 - t0;  // 0: a padding item, which only takes part in the barrier
 
     f32x4 o[MT];
 #pragma unroll
     for (int c = 0; c < MT; c++) o[c] = f32x4{0.f, 0.f, 0.f, 0.f};
     float m_run = -1e30f, l_run = 0.f;
 
-    // A ring of NS register stages, one page each: while page i is consumed the loads of pages
-    // i+1 .. i+NS-1 are in flight.
-    DecodePage<D> st[NS];
+    if (n_tok > 0) {
+        const int page0 = t0 / kBlock;
+        const int n_pg = (n_tok + kBlock - 1) / kBlock;  // 1..64
+        const int32_t *pages = A.pages + it[DC_PAGEOFF] + page0;
+        const int my_page = pages[min(lane, n_pg - 1)];  // lane i holds the id of page i of the split
+
+        x8 qreg[KS];
+        const int64_t q_off = ((int64_t)qrow * A.Hq + kvh * G + min(j, G - 1)) * D;
 #pragma unroll
-    for (int u = 0; u < NS - 1; u++)
-        if (u < n_pg) decode_fetch<D>(A, kvh, __builtin_amdgcn_readlane(my_page, u), j, g, st[u]);
-    // Main part: every page consumed here is full and every fetch is of a page of the split, so the body
-    // has no branch around the loads and the compiler's wait before a stage's first use counts exactly
-    // the loads issued after it.  (With a conditional fetch the wait has to be right for the path
-    // without it, and then also waits for the page just requested: one page in flight instead of NS - 1.)
-    int pp = 0;
-    for (; pp + 2 * (NS - 1) < n_pg; pp += NS) {
-#pragma unroll
-        for (int u = 0; u < NS; u++) {
-            decode_fetch<D>(A, kvh, __builtin_amdgcn_readlane(my_page, pp + u + NS - 1), j, g, st[(u + NS - 1) % NS]);
-            decode_consume<D, E>(A, st[u], qreg, kBlock, g, o, m_run, l_run);
+        for (int kk = 0; kk < KS; kk++) {
+            u32x4 w = *reinterpret_cast<const u32x4 *>(A.q + q_off + (4 * kk + g) * 8);
+            if (j >= G) w = u32x4{0u, 0u, 0u, 0u};
+            qreg[kk] = __builtin_bit_cast(x8, w);
         }
-    }
-    // The last pages (at most 2 NS - 2): fetch while there is a page left, the last one may be partial.
-    for (; pp < n_pg; pp += NS) {
+
+        // A ring of NS register stages, one page each: while page i is consumed the loads of pages
+        // i+1 .. i+NS-1 are in flight.
+        DecodePage<D> st[NS];
 #pragma unroll
-        for (int u = 0; u < NS; u++) {
-            const int cur = pp + u;
-            if (cur < n_pg) {
-                const int nxt = cur + NS - 1;
-                if (nxt < n_pg) decode_fetch<D>(A, kvh, __builtin_amdgcn_readlane(my_page, nxt), j, g, st[(u + NS - 1) % NS]);
-                decode_consume<D, E>(A, st[u], qreg, n_tok - cur * kBlock, g, o, m_run, l_run);
+        for (int u = 0; u < NS - 1; u++)
+            if (u < n_pg) decode_fetch<D>(A, kvh, __builtin_amdgcn_readlane(my_page, u), j, g, st[u]);
+        // Main part: every page consumed here is full and every fetch is of a page of the split, so the body
+        // has no branch around the loads and the compiler's wait before a stage's first use counts exactly
+        // the loads issued after it.  (With a conditional fetch the wait has to be right for the path
+        // without it, and then also waits for the page just requested: one page in flight instead of NS - 1.)
+        int pp = 0;
+        for (; pp + 2 * (NS - 1) < n_pg; pp += NS) {
+#pragma unroll
+            for (int u = 0; u < NS; u++) {
+                decode_fetch<D>(A, kvh, __builtin_amdgcn_readlane(my_page, pp + u + NS - 1), j, g, st[(u + NS - 1) % NS]);
+                decode_consume<D, E>(A, st[u], qreg, kBlock, g, o, m_run, l_run);
             }
         }
+        // The last pages (at most 2 NS - 2): fetch while there is a page left, the last one may be partial.
+        for (; pp < n_pg; pp += NS) {
+#pragma unroll
+            for (int u = 0; u < NS; u++) {
+                const int cur = pp + u;
+                if (cur < n_pg) {
+                    const int nxt = cur + NS - 1;
+                    if (nxt < n_pg) decode_fetch<D>(A, kvh, __builtin_amdgcn_readlane(my_page, nxt), j, g, st[(u + NS - 1) % NS]);
+                    decode_consume<D, E>(A, st[u], qreg, n_tok - cur * kBlock, g, o, m_run, l_run);
+                }
+            }
+        }
+        l_run += xor_lanes(l_run, 16);
+        l_run = half_swap_sum(l_run);
     }
-    l_run += xor_lanes(l_run, 16);
-    l_run = half_swap_sum(l_run);
-    if (j >= G) return;
+
+    // ---- team: members (positions 1 ..) hand their result to the first wave through LDS
+    // LDS: O^T of every wave [waves][G][D], then (m, l) [waves][G][2]; a lane reads back the elements it owns
+    float *const my_o = team_lds + (size_t)wave * G * D;
+    float *const my_ml = team_lds + (size_t)wg_waves * G * D + (size_t)wave * G * 2;
+    if (team_pos > 0 && j < G) {
+        float *dst = my_o + j * D + 4 * g;
+#pragma unroll
+        for (int c = 0; c < MT; c++) *reinterpret_cast<f32x4 *>(dst + 16 * c) = o[c];
+        if (g == 0) {
+            my_ml[2 * j] = m_run;
+            my_ml[2 * j + 1] = l_run;
+        }
+    }
+    __syncthreads();  // executed once by every wave of a decode workgroup
+    if (team_pos > 0 || n_tok == 0 || j >= G) return;
+    for (int i = 1; i < team_n; i++) {
+        const float m_i = my_ml[(i * G + j) * 2], l_i = my_ml[(i * G + j) * 2 + 1];
+        const float m_new = fmaxf(m_run, m_i);
+        const float a = fast_exp2(m_run - m_new), b = fast_exp2(m_i - m_new);
+        m_run = m_new;
+        l_run = l_run * a + l_i * b;
+        const float *src = my_o + (size_t)i * G * D + j * D + 4 * g;
+#pragma unroll
+        for (int c = 0; c < MT; c++) o[c] = o[c] * a + *reinterpret_cast<const f32x4 *>(src + 16 * c) * b;
+    }
     if (slot < 0) {
         const float inv = 1.f / l_run;
         uint16_t *dst = A.out + ((int64_t)qrow * A.Hq + kvh * G + j) * D + 4 * g;
@@ -883,7 +919,8 @@ __global__ void __launch_bounds__(WAVES * 64, WAVES == kMixedWaves ? 1 : kDecode
     } else {
         const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
         const int idx = ((int)blockIdx.x - A.n_prefill) * WAVES + wave;
-        if (idx < A.n_decode) decode_item<D, E>(A, decode + (int64_t)idx * kItemInts);
+        // the decode items fill whole workgroups (padding items at the end of some): every wave gets one
+        if (idx < A.n_decode) decode_item<D, E>(A, decode + (int64_t)idx * kItemInts, reinterpret_cast<float *>(lds), WAVES);
     }
 }
 
@@ -1049,7 +1086,8 @@ static int launch_attention_d(const tc_plan *p, const AttnArgs &A, int launches,
     const AttnScalars sc = {A.n_prefill, A.n_decode, A.Hq, A.Hkv, A.G, A.scale_log2};
     if (grid > 0 && p->n_pieces > 0) {
         static bool lds_ok = false;  // opt in to more than 64 KiB of dynamic LDS once per process
-        const int lds = PrefillCfg<D>::kLdsBytes;
+        const int lds = PrefillCfg<D>::kLdsBytes;  // the decode workgroups of the launch need less, for any G
+        static_assert(decode_team_lds_bytes(kMixedWaves, 16, D) <= (size_t)PrefillCfg<D>::kLdsBytes, "team buffers must fit the prefill tiles' LDS");
         if (!lds_ok) {
             hipError_t e = hipFuncSetAttribute((const void *)mixed_attention_kernel<D, E, kMixedWaves>,
                                                hipFuncAttributeMaxDynamicSharedMemorySize, lds);
@@ -1059,7 +1097,7 @@ static int launch_attention_d(const tc_plan *p, const AttnArgs &A, int launches,
         mixed_attention_kernel<D, E, kMixedWaves><<<grid, kMixedWaves * 64, lds, st>>>(A.k_pool, A.v_pool, A.q, A.out, A.pages, A.prefill,
                                                                                    A.pieces, A.decode, A.ws_o, A.ws_ml, sc);
     } else if (grid > 0) {
-        mixed_attention_kernel<D, E, kDecodeWaves><<<grid, kDecodeWaves * 64, 0, st>>>(A.k_pool, A.v_pool, A.q, A.out, A.pages, A.prefill,
+        mixed_attention_kernel<D, E, kDecodeWaves><<<grid, kDecodeWaves * 64, decode_team_lds_bytes(kDecodeWaves, p->G, D), st>>>(A.k_pool, A.v_pool, A.q, A.out, A.pages, A.prefill,
                                                                                    A.pieces, A.decode, A.ws_o, A.ws_ml, sc);
     }
     hipError_t e = hipGetLastError();

@@ -28,13 +28,21 @@ tc_status check_pool_matches(const tc_plan *plan, const tc_kv_pool *pool, bool n
     return TC_OK;
 }
 
-// Decode KV ranges are cut into equal splits so that work items are uniform; the split
-// is the largest of 1024..128 tokens that still yields enough items to fill the chip.
+// The KV range of a decode sequence is cut into the fewest splits of at most `split` tokens, equal up
+// to a page; the split is the largest of 1024..128 tokens that still yields enough items to fill the chip.
 static int choose_split(int64_t decode_token_heads) {
     const int64_t want_items = (int64_t)kNumCu * kDecodeWgPerCu * kDecodeWaves;  // one item per wavefront resident in a decode-only launch (finer splits measured slower)
     for (int split = kMaxSplitPages * kBlock; split > 128; split /= 2)
         if (decode_token_heads / split >= want_items) return split;
     return 128;
+}
+
+// First token of split i of a decode sequence of kv tokens cut into ns splits: the sequence's pages are
+// dealt out evenly (the first splits get the odd pages), so the splits of a sequence take the same time
+// and the waves that run them side by side finish together.  split_begin(kv, ns, ns) >= kv.
+static int64_t split_begin(int64_t kv, int ns, int i) {
+    const int64_t pages = (kv + kBlock - 1) / kBlock;
+    return kBlock * (i * (pages / ns) + std::min<int64_t>(i, pages % ns));
 }
 
 // When a batch has few prefill row blocks (a small chunk, as on a decode-heavy instance), each of
@@ -121,20 +129,70 @@ tc_status build_plan(const tc_kv_pool *pool, const tc_batch *b, tc_plan **out) {
     std::stable_sort(tiles.begin(), tiles.end(), [](const Tile &x, const Tile &y) { return x.cost > y.cost; });
     choose_prefill_cuts(tiles.data(), tiles.size(), Hkv, decode_tokens * Hkv * D * 4);
 
+    // ---- decode items.  Consecutive splits of one (sequence, KV head) that share a workgroup form a team:
+    // the workgroup combines their results in LDS, and the team writes the output rows itself when it
+    // holds all splits of its (sequence, KV head), else one partial result for the merge launch.  A run
+    // of W or more splits (W = waves per workgroup of the launch) fills whole workgroups first; what is
+    // left of it, like a shorter run, goes as one team into the first open workgroup with room, and when
+    // none of a bounded window of open workgroups has room, its head fills up the oldest one (one more
+    // team for that run, and no wave slot wasted).  Runs are taken longest split first.  Wave slots
+    // still free at the end hold padding items (no tokens).
+    const int W = tiles.empty() ? kDecodeWaves : kMixedWaves;
+    struct Run { int seq, h, ns, len; };  // len = tokens of the first (longest) split
+    struct Team { int seq, h, first, n, idx, wg, at; };  // splits [first, first + n) = team `idx` of its run; wave slots [at, at + n) of workgroup `wg`
+    std::vector<Run> runs;
+    for (int s = 0; s < S; s++) {
+        if (p->q_start[s + 1] - p->q_start[s] != 1) continue;
+        const int64_t kv = (int64_t)p->ctx_len[s] + 1;
+        const int ns = (int)((kv + p->split_tokens - 1) / p->split_tokens);
+        for (int h = 0; h < Hkv; h++) runs.push_back({s, h, ns, (int)std::min<int64_t>(kv, split_begin(kv, ns, 1))});
+    }
+    std::stable_sort(runs.begin(), runs.end(), [](const Run &x, const Run &y) { return x.len > y.len; });
+    std::vector<Team> teams;
+    std::vector<int> wg_fill;                        // wave slots taken, per decode workgroup
+    std::vector<int32_t> n_teams((size_t)S * Hkv, 0);  // teams per (sequence, KV head)
+    {
+        constexpr size_t kOpen = 32;
+        std::vector<int> open;  // workgroups with free wave slots, oldest first
+        auto place = [&](const Run &r, int first, int n, size_t j) {  // team into open[j]
+            const int wg = open[j];
+            teams.push_back({r.seq, r.h, first, n, n_teams[(size_t)r.seq * Hkv + r.h]++, wg, wg_fill[wg]});
+            wg_fill[wg] += n;
+            if (wg_fill[wg] == W) open.erase(open.begin() + j);
+        };
+        for (const Run &r : runs) {
+            int first = 0, left = r.ns;
+            while (left > 0) {
+                const int n = std::min(left, W);
+                size_t j = 0;
+                while (j < open.size() && (n == W || wg_fill[open[j]] + n > W)) j++;
+                int take = n;
+                if (j == open.size()) {
+                    if (n < W && open.size() == kOpen) {  // fill up the oldest open workgroup with the head of the run
+                        j = 0;
+                        take = W - wg_fill[open[0]];
+                    } else {
+                        open.push_back((int)wg_fill.size());
+                        wg_fill.push_back(0);
+                        j = open.size() - 1;
+                    }
+                }
+                place(r, first, take, j);
+                first += take;
+                left -= take;
+            }
+        }
+    }
+    int64_t n_decode_merge = 0, n_decode_partials = 0;
+    for (int32_t nt : n_teams)
+        if (nt > 1) { n_decode_merge++; n_decode_partials += nt; }
+
     // ---- section sizes
-    int64_t n_prefill = (int64_t)tiles.size() * Hkv, n_pieces = 0, n_decode = 0, n_merge = 0, n_partials = 0;
+    int64_t n_prefill = (int64_t)tiles.size() * Hkv, n_pieces = 0, n_decode = (int64_t)wg_fill.size() * W, n_merge = n_decode_merge,
+            n_partials = n_decode_partials;
     for (const Tile &t : tiles) {
         n_pieces += (int64_t)t.k * Hkv;
         if (t.k > 1) { n_merge += (int64_t)t.npos * Hkv; n_partials += (int64_t)t.k * t.npos * Hkv; }
-    }
-    for (int s = 0; s < S; s++) {
-        const int q = p->q_start[s + 1] - p->q_start[s];
-        if (q == 1) {
-            const int64_t kv = (int64_t)p->ctx_len[s] + 1;
-            const int64_t ns = (kv + p->split_tokens - 1) / p->split_tokens;
-            n_decode += ns * Hkv;
-            if (ns > 1) { n_merge += Hkv; n_partials += ns * Hkv; }
-        }
     }
     if (n_pieces + n_decode >= ((int64_t)1 << 28) || n_partials >= ((int64_t)1 << 28)) { delete p; return fail(TC_ERR_SPAN, "batch too large"); }
     p->n_prefill = (int)n_prefill; p->n_pieces = (int)n_pieces; p->n_decode = (int)n_decode; p->n_merge = (int)n_merge;
@@ -229,35 +287,37 @@ tc_status build_plan(const tc_kv_pool *pool, const tc_batch *b, tc_plan **out) {
         }
     }
 
-    // ---- decode items: longest splits first so the tail of the launch is short work.
-    struct Split { int seq, begin, end, idx, nsplit; };
-    std::vector<Split> splits;
-    std::vector<int32_t> slot0(S, -1);
-    for (int s = 0; s < S; s++) {
-        if (p->q_start[s + 1] - p->q_start[s] != 1) continue;
-        const int kv = p->ctx_len[s] + 1;
-        const int ns = (kv + p->split_tokens - 1) / p->split_tokens;
-        if (ns > 1) {
-            slot0[s] = next_slot;
-            for (int h = 0; h < Hkv; h++, mg += kItemInts) {
-                mg[MG_SEQ] = s; mg[MG_KVH] = h; mg[MG_QROW] = p->q_start[s];
-                mg[MG_SLOT0] = next_slot + h * ns; mg[MG_NSPLIT] = ns;
-            }
-            next_slot += ns * Hkv;
+    // ---- merge items of the (sequence, KV head) pairs with several teams, then the decode items
+    std::vector<int32_t> slot0((size_t)S * Hkv, -1);  // first partial slot of such a pair
+    for (int s = 0; s < S; s++)
+        for (int h = 0; h < Hkv; h++) {
+            const int nt = n_teams[(size_t)s * Hkv + h];
+            if (nt <= 1) continue;
+            slot0[(size_t)s * Hkv + h] = next_slot;
+            mg[MG_SEQ] = s; mg[MG_KVH] = h; mg[MG_QROW] = p->q_start[s]; mg[MG_SLOT0] = next_slot; mg[MG_NSPLIT] = nt;
+            mg += kItemInts;
+            next_slot += nt;
         }
-        for (int i = 0; i < ns; i++)
-            splits.push_back({s, i * p->split_tokens, std::min(kv, (i + 1) * p->split_tokens), i, ns});
+    int32_t *dc0 = H + p->off_decode;
+    for (int64_t i = 0; i < n_decode; i++) {  // padding unless overwritten below: no tokens, a team of its own
+        int32_t *dc = dc0 + i * kItemInts;
+        dc[DC_SEQ] = -1; dc[DC_SLOT] = -1; dc[DC_TEAM] = 1;
     }
-    std::stable_sort(splits.begin(), splits.end(),
-                     [](const Split &x, const Split &y) { return x.end - x.begin > y.end - y.begin; });
-    int32_t *dc = H + p->off_decode;
-    for (const Split &sp : splits)
-        for (int h = 0; h < Hkv; h++, dc += kItemInts) {
-            dc[DC_SEQ] = sp.seq; dc[DC_KVH] = h; dc[DC_BEGIN] = sp.begin; dc[DC_END] = sp.end;
-            dc[DC_QROW] = p->q_start[sp.seq];
-            dc[DC_SLOT] = sp.nsplit > 1 ? slot0[sp.seq] + h * sp.nsplit + sp.idx : -1;
-            dc[DC_PAGEOFF] = p->page_off[sp.seq];
+    for (const Team &t : teams) {
+        const int64_t kv = (int64_t)p->ctx_len[t.seq] + 1;
+        const int32_t base = slot0[(size_t)t.seq * Hkv + t.h];
+        for (int m = 0; m < t.n; m++) {
+            int32_t *dc = dc0 + ((int64_t)t.wg * W + t.at + m) * kItemInts;
+            dc[DC_SEQ] = t.seq; dc[DC_KVH] = t.h;
+            const int ns = (int)((kv + p->split_tokens - 1) / p->split_tokens);
+            dc[DC_BEGIN] = (int)split_begin(kv, ns, t.first + m);
+            dc[DC_END] = (int)std::min<int64_t>(kv, split_begin(kv, ns, t.first + m + 1));
+            dc[DC_QROW] = p->q_start[t.seq];
+            dc[DC_SLOT] = base >= 0 ? base + t.idx : -1;
+            dc[DC_PAGEOFF] = p->page_off[t.seq];
+            dc[DC_TEAM] = t.n | (m << 8);
         }
+    }
     *out = p;
     return TC_OK;
 }

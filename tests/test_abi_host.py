@@ -179,21 +179,46 @@ def check_work_list(tc, sp, table, nb):
     assert np.all(np.diff(size) <= 0)
     if 256 % Hkv == 0:  # the KV head stays the fastest index: workgroup id mod Hkv names it
         assert np.all(pf[pc[:, 0], 1] == np.arange(len(pc)) % Hkv)
-    # decode: splits tile [0, kv_len) page-aligned, <= 64 pages each
-    for s in np.flatnonzero(sp.q_len == 1):
-        it = dc[(dc[:, 0] == s) & (dc[:, 1] == 0)]
-        it = it[np.argsort(it[:, 2])]
-        assert it[0, 2] == 0 and np.all(it[1:, 2] == it[:-1, 3]) and it[-1, 3] == sp.kv_len[s]
-        assert np.all(it[:, 2] % 16 == 0) and np.all(it[:, 3] - it[:, 2] <= 1024)
-        assert np.all((it[:, 5] >= 0) == (len(it) > 1))
-    assert np.all(np.diff((dc[:, 3] - dc[:, 2])[::Hkv]) <= 0)
-    # partial slots: unique and dense over decode splits and prefill pieces together
-    slots += dc[dc[:, 5] >= 0, 5].tolist()
-    assert len(slots) == info.num_partials and sorted(slots) == list(range(info.num_partials))
-    # merge items name exactly the slots of their splits / pieces
+    # decode: the items fill whole workgroups of W waves; padding items hold no tokens
+    W_ = info.block_threads // 64
+    assert len(dc) % W_ == 0 and len(dc) == info.num_decode_items
+    real = dc[dc[:, 3] > dc[:, 2]]
+    pad = dc[dc[:, 3] == dc[:, 2]]
+    assert np.all(pad[:, 0] == -1) and np.all(pad[:, 7] == 1) and len(pad) < 32 * W_
+    # splits tile [0, kv_len) page-aligned, <= 64 pages each, for every KV head
     for s in np.flatnonzero(sp.q_len == 1):
         for h in range(Hkv):
-            mine = dc[(dc[:, 0] == s) & (dc[:, 1] == h)]
+            it = real[(real[:, 0] == s) & (real[:, 1] == h)]
+            it = it[np.argsort(it[:, 2])]
+            assert it[0, 2] == 0 and np.all(it[1:, 2] == it[:-1, 3]) and it[-1, 3] == sp.kv_len[s]
+            assert np.all(it[:, 2] % 16 == 0) and np.all(it[:, 3] - it[:, 2] <= 1024)
+            assert np.all(it[:, 4] == qs[s])
+            # a partial slot exactly when the splits are in more than one team (then one slot per team)
+            n_teams = int(np.sum(it[:, 7] >> 8 == 0))
+            assert np.all((it[:, 5] >= 0) == (n_teams > 1)) and n_teams <= -(-len(it) // W_) + 1
+    # teams: consecutive waves of one workgroup, positions 0..n-1, consecutive splits of one (sequence, KV head), one slot
+    i = 0
+    leaders = []
+    while i < len(dc):
+        n, pos = int(dc[i, 7]) & 0xFF, int(dc[i, 7]) >> 8
+        assert pos == 0 and 1 <= n <= W_ and i // W_ == (i + n - 1) // W_
+        team = dc[i:i + n]
+        assert np.all(team[:, 7] == n + 256 * np.arange(n))
+        if team[0, 3] > team[0, 2]:
+            assert np.all(team[:, 0] == team[0, 0]) and np.all(team[:, 1] == team[0, 1]) and np.all(team[:, 5] == team[0, 5])
+            assert np.all(team[1:, 2] == team[:-1, 3])
+            leaders.append(team[0])
+        else:
+            assert n == 1
+        i += n
+    leaders = np.array(leaders).reshape(-1, 8)
+    # partial slots: unique and dense over decode teams and prefill pieces together
+    slots += leaders[leaders[:, 5] >= 0, 5].tolist()
+    assert len(slots) == info.num_partials and sorted(slots) == list(range(info.num_partials))
+    # merge items name exactly the slots of their teams / pieces
+    for s in np.flatnonzero(sp.q_len == 1):
+        for h in range(Hkv):
+            mine = leaders[(leaders[:, 0] == s) & (leaders[:, 1] == h)]
             if len(mine) > 1:
                 merge_expected.append((int(s), h, int(qs[s]), int(mine[:, 5].min()), len(mine)))
                 assert sorted(mine[:, 5].tolist()) == list(range(mine[:, 5].min(), mine[:, 5].min() + len(mine)))
