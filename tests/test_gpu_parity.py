@@ -59,7 +59,13 @@ SMALL = {
     "decode_page_boundaries": (8, 2, 128, [1, 1, 1, 1, 1], [14, 15, 16, 31, 32]),
     "decode_split_boundaries": (8, 2, 128, [1, 1, 1, 1], [126, 127, 128, 255]),
     "decode_long_ragged": (32, 8, 128, [1, 1, 1], [3000, 1025, 777]),
-    "decode_more_than_64_splits": (8, 2, 128, [1, 1], [20000, 8191]),  # 157 and 64 splits of 128: two merge passes
+    # splits of 128 in teams of four: 79 and 16 partial results per (sequence, KV head): two merge passes for the first
+    "decode_more_than_64_partials": (8, 2, 128, [1, 1], [40000, 8191]),
+    # teams (splits of one sequence combined inside a workgroup) with the largest group of heads, alone and
+    # beside a prefill chunk (eight-wave workgroups), and with head_dim 64 over ragged lengths
+    "teams_g16": (16, 1, 128, [1, 1, 1], [5000, 3000, 700]),
+    "teams_g16_with_prefill": (16, 1, 128, [40, 1, 1], [10, 5000, 3000]),
+    "teams_d64_ragged": (8, 2, 64, [1, 1, 1, 1, 1, 1], [100, 129, 600, 1500, 2047, 4100]),
     "prefill_two_rows": (4, 1, 128, [2], [0]),
     "prefill_ragged_tiles": (8, 2, 128, [77], [0]),
     "prefill_offset_not_page_aligned": (8, 2, 128, [130], [37]),
