@@ -14,7 +14,8 @@ constexpr int kBlock = 16;          // tokens per KV page
 // Launch shapes of the fused attention kernel.  A batch with a prefill chunk runs workgroups of eight
 // waves, one per compute unit (two waves per SIMD, up to 256 registers each): the eight waves sweep the
 // same K/V tiles for 256 (position, head) rows, and a decode workgroup of that launch holds eight
-// independent decode items.  A batch of decodes only runs workgroups of four waves, three per compute unit.
+// decode items (one KV split per wave; splits of one sequence and KV head that share the workgroup are
+// combined there).  A batch of decodes only runs workgroups of four waves, three per compute unit.
 constexpr int kMixedWaves = 8;
 constexpr int kDecodeWaves = 4;
 constexpr int kDecodeWgPerCu = 3;

@@ -8,7 +8,8 @@
 //         workgroups [0, n_prefill)      causal chunked-prefill pieces: 8 waves = 256 (position, head) rows
 //                                        of one KV head over a range of 64-token KV tiles, MFMA 32x32x16,
 //                                        software-pipelined so that the softmax runs under the MFMAs
-//         remaining workgroups           independent wavefronts, one decode KV split each,
+//         remaining workgroups           one decode KV split per wavefront (splits of one sequence and KV head
+//                                        that share a workgroup are combined in LDS),
 //                                        MFMA 16x16x32 and 16x16x16
 //       Two shapes: 8 waves per workgroup, one workgroup per compute unit, when the batch has a prefill
 //       chunk; 4 waves, three workgroups per compute unit, for a batch of decodes only.
@@ -692,8 +693,8 @@ __device__ void prefill_item(const AttnArgs &A, const int32_t *__restrict__ it, 
 //   O^T[d][head]    += sum_token V^T[d][token] P^T[token][head]   16x16x16, contraction over the page's
 //                      16 tokens: lane feeds tokens 4g..4g+3
 // Pages resident in registers per wave: one being consumed, the rest in flight.  Two keep the
-// decode-only kernel within 168 VGPRs (three waves per SIMD); three or four measured the same
-// bandwidth, in the twelve-wave shape and in the eight-wave shape of a launch with a prefill chunk.
+// decode-only kernel within 168 VGPRs (three waves per SIMD; a third stage spills there); three or four
+// measured the same bandwidth in the eight-wave shape of a launch with a prefill chunk.
 constexpr int kDecodeStages = 2;
 
 template <int D>
