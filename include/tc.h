@@ -91,7 +91,8 @@ typedef struct {
                                         /* padding included (whole workgroups)               */
     int32_t num_merge_items;            /* (query row, KV head) pairs that need the merge    */
     int32_t num_partials;               /* partial results held in the workspace             */
-    int32_t split_tokens;               /* most KV tokens a decode split holds               */
+    int32_t split_tokens;               /* KV tokens a decode split holds at most, except that a sequence */
+                                        /* one workgroup's waves can cover with splits of up to 1024 is cut into that many */
     int32_t rows_per_prefill_item;      /* (position, head) rows per prefill workgroup       */
     int32_t grid_blocks, block_threads; /* launch shape of the fused attention kernel        */
     int64_t total_pages;                /* table entries copied                              */
@@ -120,11 +121,12 @@ tc_status tc_plan_get_info(const tc_plan *plan, tc_plan_info *info);
  *            (-1 = the piece is the whole item and writes out), pieces of the item, 0, 0, 0}
  * A batch with few prefill row blocks has their KV ranges cut into pieces that run as separate
  * workgroups; position i of such an item owns partial slots slot + i * pieces .. + pieces - 1.
- * Decode items come in workgroups of block_threads / 64 wave slots.  The splits of a sequence hold the
+ * Decode items come in workgroups of W = block_threads / 64 wave slots.  A sequence is cut into 1, 2,
+ * 4 .. W splits, or a multiple of W when W splits of 1024 tokens cannot cover it; its splits hold the
  * same number of pages up to one.  Consecutive splits of one (sequence, KV head) in one workgroup are a
  * team (consecutive items, positions 0..members-1, all carrying the team's partial_slot): the workgroup
  * combines their results, and the team writes the output rows (-1) or one partial result.  An item
- * with kv_begin = kv_end (seq = -1) is padding at the end of the list. */
+ * with kv_begin = kv_end (seq = -1) is padding. */
 tc_status tc_plan_copy_items(const tc_plan *plan, int32_t kind, int32_t *dst, size_t cap_items);
 
 /* Bytes of DEVICE scratch tc_mixed_attention needs for this plan (may be 0). */

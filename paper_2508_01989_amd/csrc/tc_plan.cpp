@@ -45,6 +45,20 @@ static int64_t split_begin(int64_t kv, int ns, int i) {
     return kBlock * (i * (pages / ns) + std::min<int64_t>(i, pages % ns));
 }
 
+// Splits of a decode sequence of kv tokens, to run in workgroups of W waves (W a power of two): pieces of
+// at most `split` tokens, their number rounded up to a power of two, so that the runs pack into
+// workgroups without gaps; a sequence that W pieces of up to kMaxSplitPages pages can cover is never cut
+// into more than W (all of them are then one team, which writes the output rows itself: no partial
+// result, no merge item); a longer one gets a multiple of W (whole workgroups).
+static int num_splits(int64_t kv, int split, int W) {
+    const int64_t ns = (kv + split - 1) / split;
+    const int64_t longest = (int64_t)kMaxSplitPages * kBlock;
+    if (kv > (int64_t)W * longest) return (int)((ns + W - 1) / W * W);
+    int n = 1;
+    while (n < ns && n < W) n *= 2;
+    return n;
+}
+
 // When a batch has few prefill row blocks (a small chunk, as on a decode-heavy instance), each of
 // them sweeps its whole KV range in one workgroup while most of the chip idles, and that sweep is the
 // iteration's critical path.  Then the KV range of a row block is cut into k pieces that run as
@@ -132,11 +146,10 @@ tc_status build_plan(const tc_kv_pool *pool, const tc_batch *b, tc_plan **out) {
     // ---- decode items.  Consecutive splits of one (sequence, KV head) that share a workgroup form a team:
     // the workgroup combines their results in LDS, and the team writes the output rows itself when it
     // holds all splits of its (sequence, KV head), else one partial result for the merge launch.  A run
-    // of W or more splits (W = waves per workgroup of the launch) fills whole workgroups first; what is
-    // left of it, like a shorter run, goes as one team into the first open workgroup with room, and when
-    // none of a bounded window of open workgroups has room, its head fills up the oldest one (one more
-    // team for that run, and no wave slot wasted).  Runs are taken longest split first.  Wave slots
-    // still free at the end hold padding items (no tokens).
+    // of W splits (W = waves per workgroup of the launch) is a workgroup of its own; shorter runs
+    // (1, 2, 4 .. splits) go as one team into the first open workgroup with room (first fit over a
+    // bounded window; the oldest is closed when none has room).  Runs are taken longest split first.
+    // Wave slots left free hold padding items (no tokens).
     const int W = tiles.empty() ? kDecodeWaves : kMixedWaves;
     struct Run { int seq, h, ns, len; };  // len = tokens of the first (longest) split
     struct Team { int seq, h, first, n, idx, wg, at; };  // splits [first, first + n) = team `idx` of its run; wave slots [at, at + n) of workgroup `wg`
@@ -144,7 +157,7 @@ tc_status build_plan(const tc_kv_pool *pool, const tc_batch *b, tc_plan **out) {
     for (int s = 0; s < S; s++) {
         if (p->q_start[s + 1] - p->q_start[s] != 1) continue;
         const int64_t kv = (int64_t)p->ctx_len[s] + 1;
-        const int ns = (int)((kv + p->split_tokens - 1) / p->split_tokens);
+        const int ns = num_splits(kv, p->split_tokens, W);
         for (int h = 0; h < Hkv; h++) runs.push_back({s, h, ns, (int)std::min<int64_t>(kv, split_begin(kv, ns, 1))});
     }
     std::stable_sort(runs.begin(), runs.end(), [](const Run &x, const Run &y) { return x.len > y.len; });
@@ -154,34 +167,22 @@ tc_status build_plan(const tc_kv_pool *pool, const tc_batch *b, tc_plan **out) {
     {
         constexpr size_t kOpen = 32;
         std::vector<int> open;  // workgroups with free wave slots, oldest first
-        auto place = [&](const Run &r, int first, int n, size_t j) {  // team into open[j]
-            const int wg = open[j];
-            teams.push_back({r.seq, r.h, first, n, n_teams[(size_t)r.seq * Hkv + r.h]++, wg, wg_fill[wg]});
-            wg_fill[wg] += n;
-            if (wg_fill[wg] == W) open.erase(open.begin() + j);
-        };
-        for (const Run &r : runs) {
-            int first = 0, left = r.ns;
-            while (left > 0) {
-                const int n = std::min(left, W);
+        for (const Run &r : runs)
+            for (int first = 0; first < r.ns; first += W) {
+                const int n = std::min(r.ns - first, W);
                 size_t j = 0;
-                while (j < open.size() && (n == W || wg_fill[open[j]] + n > W)) j++;
-                int take = n;
+                while (j < open.size() && wg_fill[open[j]] + n > W) j++;
                 if (j == open.size()) {
-                    if (n < W && open.size() == kOpen) {  // fill up the oldest open workgroup with the head of the run
-                        j = 0;
-                        take = W - wg_fill[open[0]];
-                    } else {
-                        open.push_back((int)wg_fill.size());
-                        wg_fill.push_back(0);
-                        j = open.size() - 1;
-                    }
+                    if (open.size() == kOpen) open.erase(open.begin());
+                    open.push_back((int)wg_fill.size());
+                    wg_fill.push_back(0);
+                    j = open.size() - 1;
                 }
-                place(r, first, take, j);
-                first += take;
-                left -= take;
+                const int wg = open[j];
+                teams.push_back({r.seq, r.h, first, n, n_teams[(size_t)r.seq * Hkv + r.h]++, wg, wg_fill[wg]});
+                wg_fill[wg] += n;
+                if (wg_fill[wg] == W) open.erase(open.begin() + j);
             }
-        }
     }
     int64_t n_decode_merge = 0, n_decode_partials = 0;
     for (int32_t nt : n_teams)
@@ -309,7 +310,7 @@ tc_status build_plan(const tc_kv_pool *pool, const tc_batch *b, tc_plan **out) {
         for (int m = 0; m < t.n; m++) {
             int32_t *dc = dc0 + ((int64_t)t.wg * W + t.at + m) * kItemInts;
             dc[DC_SEQ] = t.seq; dc[DC_KVH] = t.h;
-            const int ns = (int)((kv + p->split_tokens - 1) / p->split_tokens);
+            const int ns = num_splits(kv, p->split_tokens, W);
             dc[DC_BEGIN] = (int)split_begin(kv, ns, t.first + m);
             dc[DC_END] = (int)std::min<int64_t>(kv, split_begin(kv, ns, t.first + m + 1));
             dc[DC_QROW] = p->q_start[t.seq];

@@ -193,9 +193,12 @@ def check_work_list(tc, sp, table, nb):
             assert it[0, 2] == 0 and np.all(it[1:, 2] == it[:-1, 3]) and it[-1, 3] == sp.kv_len[s]
             assert np.all(it[:, 2] % 16 == 0) and np.all(it[:, 3] - it[:, 2] <= 1024)
             assert np.all(it[:, 4] == qs[s])
-            # a partial slot exactly when the splits are in more than one team (then one slot per team)
+            # 1, 2, 4 .. W splits (one team), or a multiple of W when W splits of 1024 tokens cannot cover the sequence
             n_teams = int(np.sum(it[:, 7] >> 8 == 0))
-            assert np.all((it[:, 5] >= 0) == (n_teams > 1)) and n_teams <= -(-len(it) // W_) + 1
+            assert len(it) in (1, 2, 4, 8)[:W_.bit_length()] if sp.kv_len[s] <= W_ * 1024 else len(it) % W_ == 0
+            assert n_teams == -(-len(it) // W_)
+            # a partial slot exactly when the splits are in more than one team (then one slot per team)
+            assert np.all((it[:, 5] >= 0) == (n_teams > 1))
     # teams: consecutive waves of one workgroup, positions 0..n-1, consecutive splits of one (sequence, KV head), one slot
     i = 0
     leaders = []

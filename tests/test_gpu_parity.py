@@ -245,7 +245,7 @@ def test_two_launch_form_equals_the_single_call(H):
     the merge alone must leave rows of unsplit sequences untouched."""
     import paper_2508_01989_amd as tc
     import torch
-    for name, q_len, ctx in [("split", [300, 1, 1, 1], [100, 2000, 50, 700]), ("nosplit", [40, 1, 1], [0, 30, 90])]:
+    for name, q_len, ctx in [("split", [300, 1, 1, 1], [100, 9000, 50, 700]), ("nosplit", [40, 1, 1], [0, 30, 90])]:
         b = W.make_batch(W.custom_spec("two_" + name, 32, 8, 128, q_len, ctx, seed=78))
         db = H.DeviceBatch(b)
         assert (db.plan.workspace_bytes > 0) == (name == "split")
@@ -318,7 +318,7 @@ def test_chunked_prefill_matches_one_shot_on_gpu(H):
 def test_empty_batch_and_runtime_argument_errors(H):
     import paper_2508_01989_amd as tc
     import torch
-    b = W.make_batch(W.custom_spec("err", 8, 2, 128, [1, 1], [600, 20], seed=2))
+    b = W.make_batch(W.custom_spec("err", 8, 2, 128, [1, 1], [6000, 20], seed=2))
     db = H.DeviceBatch(b)
     assert db.plan.workspace_bytes > 0
     with pytest.raises(tc.TcError) as e:
