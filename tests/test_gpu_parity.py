@@ -271,6 +271,34 @@ def test_two_launch_form_equals_the_single_call(H):
     assert e.value.status == tc.TC_ERR_NULL
 
 
+def test_graph_replays_equal_the_eager_step(H):
+    """The step (append, attention with teams, merge) captured in a HIP graph: every replay, with eager work
+    and synchronisations between the replays, gives the eager result bit for bit, pools included."""
+    import torch
+    b = W.make_batch(W.custom_spec("graph", 32, 8, 128, [300, 1, 1, 1, 1], [100, 9000, 50, 700, 3000], seed=79))
+    stream = torch.cuda.Stream()
+    with torch.cuda.stream(stream):
+        db = H.DeviceBatch(b, stream=stream)
+        assert db.plan.info.num_merge_items > 0
+        db.step()
+        torch.cuda.synchronize()
+        eager, (ek, ev) = H.to_host(db.out).copy(), db.pools_host()
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(g, stream=stream):
+            db.append()
+            db.attention()
+        for rep in range(4):
+            db.out.fill_(0)
+            db.workspace.fill_(0xFF)
+            torch.cuda.synchronize()
+            g.replay()
+            torch.cuda.synchronize()
+            assert np.array_equal(H.to_host(db.out), eager), f"replay {rep}"
+            db.step()  # eager work between the replays
+        gk, gv = db.pools_host()
+        assert np.array_equal(gk, ek) and np.array_equal(gv, ev)
+
+
 def test_block_table_relabelling_is_bitwise_invisible(H):
     b = W.make_batch(W.custom_spec("perm", 8, 2, 128, [100, 1, 1], [60, 300, 31], seed=5))
     db = H.DeviceBatch(b)
