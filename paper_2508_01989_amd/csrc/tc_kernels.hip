@@ -263,7 +263,7 @@ struct PrefillCfg {
     // 96 KiB at D = 128 with three stages, 128 KiB with four.
     static constexpr int kStages = TC_PREFILL_STAGES;
     static_assert(kStages == 3 || kStages == 4, "the page-id pipeline below is written for 3 or 4 stages");
-    static constexpr int kIdSlots = kStages - 2;  // page ids in flight per wave
+    static constexpr int kIdSlots = kStages - 2;  // page ids in flight per copying wave and tensor
     static constexpr int kLdsBytes = 2 * kStages * kTileBytes + kMixedWaves * kIdSlots * 64 * 4;
 };
 
@@ -285,8 +285,8 @@ __device__ __forceinline__ int prefill_page_id(const int32_t *__restrict__ pages
     return pages[min(tile * PrefillCfg<D>::kTilePages + page_in_tile, n_pages - 1)];
 }
 
-// Tile copies.  The 8 waves of a workgroup share every tile: waves 0-3 copy the four K pages of a
-// tile, waves 4-7 its four V^T pages, each with direct-to-LDS loads: lane L deposits its 16 bytes at
+// Tile copies.  The 8 waves of a workgroup share every tile.  A copier moves one page of a tile (copier
+// index 0-3: the four K pages, 4-7: the four V^T pages) with direct-to-LDS loads: lane L deposits its 16 bytes at
 // (wave-uniform base) + 16 L, so each load copies a 1 KiB run; the runs of a page are contiguous both
 // in the pool and in LDS, so they share one address register and one LDS base and differ only in the
 // instruction's immediate offset.  K pages are copied verbatim.  A V^T page is copied row by row
@@ -304,8 +304,8 @@ struct TileCopier {
     int64_t page_stride;  // elements per page (all KV heads)
     bool is_v;
     int page_in_tile;
-    __device__ __forceinline__ TileCopier(const AttnArgs &A, int kvh, char *lds_k, char *lds_v, int wave, int lane) {
-        static_assert(2 * C::kTilePages == kMixedWaves, "one wave per page of a tile and tensor");
+    __device__ __forceinline__ TileCopier(const AttnArgs &A, int kvh, char *lds_k, char *lds_v, int wave, int lane) {  // wave = copier index
+        static_assert(2 * C::kTilePages == kMixedWaves, "the waves 0 .. kTilePages - 1 are the older wave of each SIMD");
         static_assert(C::kTileTokens == kPrefillTileTokens, "the planner cuts KV ranges in units of this tile");
         is_v = wave >= C::kTilePages;
         page_in_tile = wave & (C::kTilePages - 1);
@@ -461,8 +461,12 @@ __device__ __forceinline__ float next_reference_max(float m_run, float row_max_l
 // register for the next phase follows that MFMA, a whole phase ahead of its use.  The 8 waves share
 // the K/V tiles; a tile is copied two steps ahead of its first use, so one barrier per tile suffices
 // and no wave waits for a copy:
-//   step j:  barrier | copy K(j+3) (waves 0-3), V(j+2) (waves 4-7) | phase 2j | phase 2j + 1
-//            | wait for the copies this wave issued in step j - 1
+//   step j:  barrier | waves 0-3: copy K(j+3) and V(j+2) | phase 2j | phase 2j + 1
+//            | waves 0-3: wait for the copies issued in step j - 1
+// Waves 0-3 are the older wave of their SIMDs: the hardware issues their instructions first, they finish
+// a step's phases early and would wait at the barrier, so the copies cost them nothing, while waves 4-7,
+// which set the pace, are spared them (1 % on a long sweep; copies by waves 4-7 alone measured 0.2 %
+// slower than one tensor per wave group).
 template <int D, class E>
 __device__ void prefill_item(const AttnArgs &A, const int32_t *__restrict__ it, const int32_t *__restrict__ pc, char *lds) {
     using C = PrefillCfg<D>;
@@ -511,26 +515,36 @@ __device__ void prefill_item(const AttnArgs &A, const int32_t *__restrict__ it, 
     float l_run = 0.f;     // running sum of this lane's half of the row
 
     // ---- prologue: tile j of the sweep lives in stage j mod NS of its tensor.  K(0..NS-1) and V(0..NS-2)
-    // are copied here; step j then copies K(j+NS) and V(j+NS-1).  `ahead` = how far this wave's copy of a
-    // step runs ahead of the step's own tile.
+    // are copied here; step j then copies K(j+NS) and V(j+NS-1).
     constexpr int NS = C::kStages;
-    const TileCopier<D> cp(A, kvh, lds_k, lds_v, wave, lane);
-    const int ahead = cp.is_v ? NS - 1 : NS;
+    // Waves 0-3 copy both tensors: wave w page w of the K tile and of the V tile.  Waves 4-7 issue no loads.
+    const bool copier = wave < C::kTilePages;
+    const TileCopier<D> cpk(A, kvh, lds_k, lds_v, wave & (C::kTilePages - 1), lane);
+    const TileCopier<D> cpv(A, kvh, lds_k, lds_v, (wave & (C::kTilePages - 1)) + C::kTilePages, lane);
+    const int pg = cpk.page_in_tile;
+    int idk_cur = 0, idv_cur = 0;  // pages this wave copies in step 0
+    // The page ids for the copies of step j are fetched in step j - (NS - 2) into slot j mod (NS - 2) of this
+    // wave (K ids, then V ids); those of steps 1 .. NS - 3 are fetched here.
+    char *const idk_slots = lds + 2 * NS * C::kTileBytes + (2 * wave) * (C::kIdSlots * kIdSlotBytes);
+    char *const idv_slots = idk_slots + C::kIdSlots * kIdSlotBytes;
+    if (copier) {
 #pragma unroll
-    for (int t = 0; t < NS - 1; t++) cp.copy(prefill_page_id<D>(pages, n_pages, t_begin + t, cp.page_in_tile), t);
-    if (!cp.is_v) cp.copy(prefill_page_id<D>(pages, n_pages, t_begin + NS - 1, cp.page_in_tile), NS - 1);
-    int id_cur = prefill_page_id<D>(pages, n_pages, t_begin + ahead, cp.page_in_tile);  // page this wave copies in step 0
-    // The page id for the copy of step j is fetched in step j - (NS - 2) into slot j mod (NS - 2) of this
-    // wave; those of steps 1 .. NS - 3 are fetched here.
-    char *const id_slots = lds + 2 * NS * C::kTileBytes + wave * (C::kIdSlots * kIdSlotBytes);
+        for (int t = 0; t < NS - 1; t++) {
+            cpk.copy(prefill_page_id<D>(pages, n_pages, t_begin + t, pg), t);
+            cpv.copy(prefill_page_id<D>(pages, n_pages, t_begin + t, pg), t);
+        }
+        cpk.copy(prefill_page_id<D>(pages, n_pages, t_begin + NS - 1, pg), NS - 1);
+        idk_cur = prefill_page_id<D>(pages, n_pages, t_begin + NS, pg);
+        idv_cur = prefill_page_id<D>(pages, n_pages, t_begin + NS - 1, pg);
 #pragma unroll
-    for (int t = 1; t < C::kIdSlots; t++)
-        page_id_fetch(pages + min((t_begin + t + ahead) * C::kTilePages + cp.page_in_tile, n_pages - 1), id_slots + t * kIdSlotBytes);
-    wait_all_loads();
-    if (cp.is_v) {
+        for (int t = 1; t < C::kIdSlots; t++) {
+            page_id_fetch(pages + min((t_begin + t + NS) * C::kTilePages + pg, n_pages - 1), idk_slots + t * kIdSlotBytes);
+            page_id_fetch(pages + min((t_begin + t + NS - 1) * C::kTilePages + pg, n_pages - 1), idv_slots + t * kIdSlotBytes);
+        }
+        wait_all_loads();
 #pragma unroll
         for (int t = 0; t < NS - 1; t++)
-            if ((t_begin + t + 1) * C::kTileTokens > kv_len) prefill_fix_tail<D>(lds_v + t * C::kTileBytes, t_begin + t, cp.page_in_tile, lane, kv_len);
+            if ((t_begin + t + 1) * C::kTileTokens > kv_len) prefill_fix_tail<D>(lds_v + t * C::kTileBytes, t_begin + t, pg, lane, kv_len);
     }
     __syncthreads();
     x8 kf[KS];     // K fragments of the half whose scores are computed next
@@ -612,25 +626,27 @@ __device__ void prefill_item(const AttnArgs &A, const int32_t *__restrict__ it, 
         // have both operand addresses in registers here, outside the scheduled regions below
         asm volatile("" : "+v"(k_nxt), "+v"(v_cur));
         __syncthreads();  // every wave is done with step j - 1; the copies issued in step j - (NS - 1) are visible
-        if (NEXT) {
-            // first the page id for the copy of step j + NS - 2, then this step's copy: K(j+NS) replaces K(j),
+        if (NEXT && copier) {
+            // first the page ids for the copies of step j + NS - 2, then this step's copies: K(j+NS) replaces K(j),
             // V(j+NS-1) replaces V(j-1).  Past the end of the range the page index is clamped and the copy
             // is never read.
-            page_id_fetch(pages + min((tile + NS - 2 + ahead) * C::kTilePages + cp.page_in_tile, n_pages - 1),
-                          id_slots + id_slot * kIdSlotBytes);
-            cp.copy(id_cur, cp.is_v ? sm1 : s0);
+            page_id_fetch(pages + min((tile + NS - 2 + NS) * C::kTilePages + pg, n_pages - 1), idk_slots + id_slot * kIdSlotBytes);
+            page_id_fetch(pages + min((tile + NS - 2 + NS - 1) * C::kTilePages + pg, n_pages - 1), idv_slots + id_slot * kIdSlotBytes);
+            cpk.copy(idk_cur, s0);
+            cpv.copy(idv_cur, sm1);
         }
         const std::true_type yes;
         phase(v_cur, 0, k_nxt, 0, sc, sn, tile * C::kTileTokens + 32, mask_tag, yes, next_tag);
         phase(v_cur, 1, k_nxt, 1, sn, sc, (tile + 1) * C::kTileTokens, mask_tag, next_tag, next_tag);
-        if (NEXT) {
+        if (NEXT && copier) {
             // loads return in order: all but the copies of the last NS - 2 steps and the page ids fetched
-            // after the one for step j + 1 have landed, i.e. that page id and the copies of step j - (NS - 2)
-            wait_loads_but<(NS - 2) * (C::kRuns + 1) - 1>();
+            // after those for step j + 1 have landed, i.e. those page ids and the copies of step j - (NS - 2)
+            wait_loads_but<(NS - 2) * (2 * C::kRuns + 2) - 2>();
             id_slot = id_slot == C::kIdSlots - 1 ? 0 : id_slot + 1;  // slot of step j + 1
-            id_cur = page_id_read(id_slots + id_slot * kIdSlotBytes, lane);
-            if (decltype(mask_tag)::value && cp.is_v && (tile + 2) * C::kTileTokens > kv_len)
-                prefill_fix_tail<D>(lds_v + s1 * C::kTileBytes, tile + 1, cp.page_in_tile, lane, kv_len);
+            idk_cur = page_id_read(idk_slots + id_slot * kIdSlotBytes, lane);
+            idv_cur = page_id_read(idv_slots + id_slot * kIdSlotBytes, lane);
+            if (decltype(mask_tag)::value && (tile + 2) * C::kTileTokens > kv_len)
+                prefill_fix_tail<D>(lds_v + s1 * C::kTileBytes, tile + 1, pg, lane, kv_len);
         }
         s0 = s1;
     };
