@@ -66,6 +66,10 @@ SMALL = {
     "teams_g16": (16, 1, 128, [1, 1, 1], [5000, 3000, 700]),
     "teams_g16_with_prefill": (16, 1, 128, [40, 1, 1], [10, 5000, 3000]),
     "teams_d64_ragged": (8, 2, 64, [1, 1, 1, 1, 1, 1], [100, 129, 600, 1500, 2047, 4100]),
+    # long ranges: one decode over 200k tokens (49 teams of four full-length splits), and a small chunk at
+    # the end of a 100k-token prompt (eight pieces of ~200 tiles each)
+    "decode_200k_tokens": (8, 2, 128, [1], [200000]),
+    "chunk_after_100k_tokens": (8, 2, 128, [64], [100000]),
     "prefill_two_rows": (4, 1, 128, [2], [0]),
     "prefill_ragged_tiles": (8, 2, 128, [77], [0]),
     "prefill_offset_not_page_aligned": (8, 2, 128, [130], [37]),
