@@ -421,10 +421,10 @@ struct PrefillWave {
         return half_swap_max(mx);
     }
     // p = 2^(s * c - m), rounded to the element type as the B operand of the second product (one
-    // operand per page); the row sum accumulates the unrounded values.  (Summing the rounded pairs with
+    // operand per page); psum = this lane's sum of the unrounded values.  (Summing the rounded pairs with
     // one dot-product instruction per pair measured 9 % slower.)
-    static __device__ __forceinline__ void probs(const f32x16 &s, float c_log2, float m_run, x8 (&pb)[2], float &l_run) {
-        float psum = 0.f;
+    static __device__ __forceinline__ void probs(const f32x16 &s, float c_log2, float m_run, x8 (&pb)[2], float &psum) {
+        psum = 0.f;
 #pragma unroll
         for (int b = 0; b < 2; b++)
 #pragma unroll
@@ -433,7 +433,6 @@ struct PrefillWave {
                 psum += pv;
                 pb[b][e] = (el)pv;
             }
-        l_run += psum;
     }
     // O^T += V^T P^T over 32 tokens
     static __device__ __forceinline__ void pv(const x8 (&vf)[2][MT], const x8 (&pb)[2], f32x16 (&o)[MT]) {
@@ -444,11 +443,15 @@ struct PrefillWave {
     }
 };
 
-// The reference maximum of a row (log2 domain) is kept until the row's true maximum exceeds it by more
-// than this slack: probabilities then reach at most 2^kMaxSlack instead of 1, which fp32 sums and 16-bit
-// operands hold without loss of relative precision, and O has to be rescaled only a few times per sweep
-// instead of whenever any of a wave's 32 rows sees a new maximum.
+// The reference maximum of a row (log2 domain) is kept while it serves: probabilities may exceed 1 as long
+// as fp32 sums and 16-bit operands hold them without loss of relative precision, so O has to be rescaled
+// only a few times per sweep instead of whenever any of a wave's 32 rows sees a new maximum, and the row
+// maxima themselves need not be computed per tile.  The probabilities of a half-tile are computed with
+// the reference as it is; if a lane's sum of them exceeds kSumLimit (some probability is above 2^9), the
+// wave computes the true row maxima of that half-tile, moves the reference of every row whose maximum
+// exceeds it by more than kMaxSlack, and computes the probabilities again (`settle` in prefill_item).
 constexpr float kMaxSlack = 8.f;
+constexpr float kSumLimit = 8192.f;  // 16 probabilities of at most 2^9
 __device__ __forceinline__ float next_reference_max(float m_run, float row_max_log2) {
     return row_max_log2 > m_run + kMaxSlack ? row_max_log2 : m_run;
 }
@@ -561,44 +564,50 @@ __device__ void prefill_item(const AttnArgs &A, const int32_t *__restrict__ it, 
 #pragma unroll
         for (int e = 0; e < 8; e++) pb[b][e] = (el)0.f;
     if (t_begin * C::kTileTokens + 31 > wave_pmin) W::causal_mask(sc, t_begin * C::kTileTokens, hh, p_abs);
-    float m_new = next_reference_max(m_run, W::row_max(sc) * c_log2);
-    float alpha_o = 1.f;  // factor O still has to be multiplied with before the next P V product
+    m_run = next_reference_max(m_run, W::row_max(sc) * c_log2);  // the first half-tile's true maxima
+    float psum = 0.f;  // this lane's sum of the probabilities just computed
 
-    // One phase, for half-tile h: `cur` holds its scores S(h) (their maxima already in m_new), `kf` the K
-    // fragments of half h + 1, `vf` / `pb` the V^T fragments and probabilities of half h - 1.
-    //   matrix cores:  S(h+1) = K(h+1) Q^T  (QK),   O += V(h-1)^T P(h-1)^T
-    //   vector ALU:    P(h) = 2^(S(h) c - m)  under those MFMAs, then the row maxima of S(h+1)
-    //   LDS:           every MFMA is followed by the read that refills its operand register for the next
-    //                  phase: K fragments of half h + 2 (KREAD), V^T fragments of half h
-    // O is relative to the maximum its last product used; the factor that brings it to the current one is
-    // applied (rarely, wave-uniform branch) just before the next product.
-    // MASK: half h + 1 may reach past a row's own position or past the last token.  Without MASK the
-    // phase is, apart from that branch, one straight line of code.
-    auto phase = [&](lds_cptr v_h, int hv, lds_cptr k_after, int hk, f32x16 &cur, f32x16 &nxt, int tok_nxt, auto mask_tag,
-                     auto qk_tag, auto kread_tag) {
-        constexpr bool MASK = decltype(mask_tag)::value, QK = decltype(qk_tag)::value, KREAD = decltype(kread_tag)::value;
-        if (__builtin_amdgcn_ballot_w64(alpha_o != 1.f) != 0) {
+    // After the probabilities `pb` of a half-tile with scores `s_pb`, and after the product of the half
+    // before it: the reference maximum served if no lane's sum got out of hand; else (rare, wave-uniform
+    // branch) move it for the rows that need it, bring O and l to the new reference and compute the
+    // probabilities again.
+    auto settle = [&](const f32x16 &s_pb) {
+        if (__builtin_amdgcn_ballot_w64(!(psum <= kSumLimit)) != 0) {
+            const float m_new = next_reference_max(m_run, W::row_max(s_pb) * c_log2);
+            const float a = fast_exp2(m_run - m_new);
+            m_run = m_new;
+            l_run *= a;
 #pragma unroll
             for (int c = 0; c < MT; c++)
 #pragma unroll
-                for (int r = 0; r < 16; r++) o[c][r] *= alpha_o;
+                for (int r = 0; r < 16; r++) o[c][r] *= a;
+            W::probs(s_pb, c_log2, m_run, pb, psum);
         }
-        alpha_o = fast_exp2(m_run - m_new);  // 1 unless this row's reference maximum moved
-        m_run = m_new;
-        l_run *= alpha_o;
+        l_run += psum;
+    };
+
+    // One phase, for half-tile h: `cur` holds its scores S(h), `kf` the K fragments of half h + 1, `vf` /
+    // `pb` the V^T fragments and probabilities of half h - 1.
+    //   matrix cores:  S(h+1) = K(h+1) Q^T  (QK),   O += V(h-1)^T P(h-1)^T
+    //   vector ALU:    P(h) = 2^(S(h) c - m)  under those MFMAs; then `settle`
+    //   LDS:           every MFMA is followed by the read that refills its operand register for the next
+    //                  phase: K fragments of half h + 2 (KREAD), V^T fragments of half h
+    // MASK: half h + 1 may reach past a row's own position or past the last token.  Without MASK the
+    // phase is, apart from the branch in `settle`, one straight line of code.
+    auto phase = [&](lds_cptr v_h, int hv, lds_cptr k_after, int hk, f32x16 &cur, f32x16 &nxt, int tok_nxt, auto mask_tag,
+                     auto qk_tag, auto kread_tag) {
+        constexpr bool MASK = decltype(mask_tag)::value, QK = decltype(qk_tag)::value, KREAD = decltype(kread_tag)::value;
         if (QK) W::qk(kf, qreg, nxt);
         if (KREAD) W::load_k(k_after, hk, kf);
         W::pv(vf, pb, o);
         W::load_v(v_h, hv, vf);
-        W::probs(cur, c_log2, m_run, pb, l_run);
+        W::probs(cur, c_log2, m_run, pb, psum);
         if (MASK && QK) W::causal_mask(nxt, tok_nxt, hh, p_abs);
-        if (QK) m_new = next_reference_max(m_run, W::row_max(nxt) * c_log2);
         // the probabilities are used by the next phase: have them computed in this one
-        asm volatile("" : "+v"(pb[0]), "+v"(pb[1]), "+v"(l_run), "+v"(m_new));
+        asm volatile("" : "+v"(pb[0]), "+v"(pb[1]), "+v"(psum));
         if (!MASK && QK && KREAD) {
             // per MFMA: the read that refills its operand, then softmax work, two elements at a time (spreading
-            // it evenly over all MFMAs of the phase measured 6 % slower); the row maxima of the new scores go
-            // under the last MFMAs of the second product
+            // it evenly over all MFMAs of the phase measured 6 % slower)
             constexpr int kMfma = KS + 2 * MT;
 #pragma unroll
             for (int g = 0; g < kMfma; g++) {
@@ -613,6 +622,7 @@ __device__ void prefill_item(const AttnArgs &A, const int32_t *__restrict__ it, 
                 }
             }
         }
+        settle(cur);
     };
     // One step for tile t_begin + j, which lives in stage s0 = j mod NS: `sc` holds the scores of its first
     // half, `kf` the K fragments of its second half.  NEXT: tile j + 1 exists.
@@ -662,10 +672,6 @@ __device__ void prefill_item(const AttnArgs &A, const int32_t *__restrict__ it, 
         step(j, yes, no);
     }
     // the product of the last half
-#pragma unroll
-    for (int c = 0; c < MT; c++)
-#pragma unroll
-        for (int r = 0; r < 16; r++) o[c][r] *= alpha_o;
     W::pv(vf, pb, o);
 
     const float l = half_swap_sum(l_run);
