@@ -606,19 +606,19 @@ __device__ void prefill_item(const AttnArgs &A, const int32_t *__restrict__ it, 
         // the probabilities are used by the next phase: have them computed in this one
         asm volatile("" : "+v"(pb[0]), "+v"(pb[1]), "+v"(psum));
         if (!MASK && QK && KREAD) {
-            // per MFMA: the read that refills its operand, then softmax work, two elements at a time (spreading
-            // it evenly over all MFMAs of the phase measured 6 % slower)
+            // per MFMA: the read that refills its operand; under ten of the phase's MFMAs, from the sixth on, softmax
+            // work for two elements each (measured against it on a long sweep: under the first ten 1.2 % slower,
+            // under the last ten 0.6 %, one element under every MFMA 2 %, three under the first eight 3.5 %)
             constexpr int kMfma = KS + 2 * MT;
+            constexpr int kProb = kMfma >= 16 ? 10 : kMfma - 2, kFirst = kMfma - kProb - 1, kPer = (16 + kProb - 1) / kProb;
 #pragma unroll
             for (int g = 0; g < kMfma; g++) {
                 __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
                 __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
-                if (g < kMfma - 4) {
-                    __builtin_amdgcn_sched_group_barrier(0x002, (16 + kMfma - 5) / (kMfma - 4), 0);
-                    __builtin_amdgcn_sched_group_barrier(0x400, (16 + kMfma - 5) / (kMfma - 4), 0);
-                    __builtin_amdgcn_sched_group_barrier(0x002, (24 + kMfma - 5) / (kMfma - 4), 0);
-                } else {
-                    __builtin_amdgcn_sched_group_barrier(0x002, 4, 0);
+                if (g >= kFirst && g < kFirst + kProb) {
+                    __builtin_amdgcn_sched_group_barrier(0x002, kPer, 0);
+                    __builtin_amdgcn_sched_group_barrier(0x400, kPer, 0);
+                    __builtin_amdgcn_sched_group_barrier(0x002, kPer, 0);
                 }
             }
         }
