@@ -27,8 +27,8 @@ from .instance import Cluster, make_request
 
 SHAPE, LAYERS = (32, 8, 128), 32
 
-# per layer: attention fit (t_fixed 14 us, t_pair 15 ps, t_kv_token 0.64 ns) + dense-layer assumptions
-DEFAULT_CM = dict(layers=LAYERS, t_fixed=14e-6 + 86e-6, t_token=0.4e-6, t_pair=1.5e-11, t_kv_token=6.4e-10)
+# per layer: attention fit (t_fixed 14 us, t_pair 14 ps, t_kv_token 0.64 ns) + dense-layer assumptions
+DEFAULT_CM = dict(layers=LAYERS, t_fixed=14e-6 + 86e-6, t_token=0.4e-6, t_pair=1.4e-11, t_kv_token=6.4e-10)
 
 SYSTEMS = {
     # name: (kinds, chunk sizes) for four instances
