@@ -90,20 +90,38 @@ typedef struct {
     int32_t num_decode_items;           /* wave slots of the decode branch: one KV split each, */
                                         /* padding included (whole workgroups)               */
     int32_t num_merge_items;            /* (query row, KV head) pairs that need the merge    */
-    int32_t num_partials;               /* partial results held in the workspace             */
+    int32_t num_partials;               /* partial results of decode teams held in the workspace */
     int32_t split_tokens;               /* KV tokens a decode split holds at most, except that a sequence */
                                         /* one workgroup's waves can cover with splits of up to 1024 is cut into that many */
     int32_t rows_per_prefill_item;      /* (position, head) rows per prefill workgroup       */
     int32_t grid_blocks, block_threads; /* launch shape of the fused attention kernel        */
     int64_t total_pages;                /* table entries copied                              */
-    int32_t num_prefill_pieces;         /* prefill workgroups: an item whose KV range is cut  */
-                                        /* runs as several pieces, else as one               */
+    int32_t num_prefill_pieces;         /* an item whose KV range is cut is several pieces, else one */
+    int32_t num_prefill_workgroups;     /* each runs one or more pieces, one after the other */
+    int32_t num_counters;               /* arrival counters of split (row, KV head) pairs    */
+    int32_t num_piece_partials;         /* partial results of pieces of cut prefill items    */
+    int32_t decode_queue;               /* 1: the decode items are drawn from a queue, in units of one workgroup's   */
+                                        /* worth, by grid_blocks - num_prefill_workgroups decode workgroups and by   */
+                                        /* the prefill workgroups once their pieces are done (levelled chunks)       */
+    int32_t reserved_;
+    int64_t build_ns;                   /* host time of the latest work-list build ...       */
+    int64_t upload_ns;                  /* ... and of enqueueing its copy to the device      */
 } tc_plan_info;
 
 /* Validate the batch against the pool shape, build the work list and upload it on
  * `stream` (one host-to-device copy).  pool->k_pool / v_pool are not touched.
  * An empty batch (num_seqs == 0) gives a valid plan whose calls are no-ops. */
 tc_status tc_plan_create(const tc_kv_pool *pool, const tc_batch *batch, void *stream, tc_plan **out);
+
+/* Re-plan an existing plan object for the next iteration's batch (paper Sec. 3.2: the batch changes
+ * every iteration; the scheduler forms it on the CPU).  Same validation, work list and errors as
+ * tc_plan_create, but the object's host and device buffers are reused and only grow when a work list
+ * is larger than any before it: in steady state the call allocates and frees nothing, builds the list
+ * in pinned host memory and enqueues one asynchronous copy on `stream`.  Calls that used the plan
+ * before must have been enqueued on the same stream (or have finished): the copy overwrites the work
+ * list they read.  After an error the plan describes an empty batch (every call on it is a no-op).
+ * A host-only plan (tc_plan_create_host) is rebuilt on the host. */
+tc_status tc_plan_update(tc_plan *plan, const tc_kv_pool *pool, const tc_batch *batch, void *stream);
 
 /* Same validation and work list, host side only (no GPU needed, nothing uploaded).
  * Such a plan can be inspected but the compute calls reject it with TC_ERR_ARG. */
@@ -112,15 +130,25 @@ tc_status tc_plan_create_host(const tc_kv_pool *pool, const tc_batch *batch, tc_
 tc_status tc_plan_get_info(const tc_plan *plan, tc_plan_info *info);
 
 /* Copy work items to HOST memory for inspection: kind 0 = prefill items, 1 = decode, 2 = merge,
- * 3 = prefill pieces; 8 int32 per item, at most cap_items items.  Fields:
+ * 3 = prefill pieces; 8 int32 per item, at most cap_items items.  Kind 4 = index of the first piece of
+ * every prefill workgroup, one int32 each.  Fields:
  *   prefill {seq, kv_head, first_local_pos, num_pos, q_row0, ctx, page_off, num_pages}
  *   decode  {seq, kv_head, kv_begin, kv_end, q_row, partial_slot (-1 = writes out), page_off,
- *            team members | position in team << 8}
- *   merge   {seq, kv_head, q_row, first_partial_slot, num_partials, 0, 0, 0}
- *   piece   {prefill item, first 64-token KV tile, end tile, partial slot of the item's first position
- *            (-1 = the piece is the whole item and writes out), pieces of the item, 0, 0, 0}
- * A batch with few prefill row blocks has their KV ranges cut into pieces that run as separate
- * workgroups; position i of such an item owns partial slots slot + i * pieces .. + pieces - 1.
+ *            team members | position in team << 4 | (split ends with the newest token) << 7 |
+ *            (index of the pair's merge item + 1) << 8}
+ *   merge   {seq, kv_head, first q_row, first partial slot or piece region, num_partials, arrival counter, rows,
+ *            prefill item or -1}: a split (sequence, KV head) pair.  A decode sequence: 1 row, its teams' partial
+ *            results in consecutive slots.  A cut prefill item (these come first): its positions, its pieces'
+ *            partial results in consecutive piece regions.
+ *   piece   {prefill item, first 64-token KV tile, end tile, first piece region of the item (-1 = the piece is
+ *            the whole item and writes out), pieces of the item, index of the piece in the item,
+ *            arrival counter (-1), 1 if it is the last piece of its workgroup}
+ * The KV range of a prefill item (a block of query rows of one KV head) may be cut into pieces: when the
+ * batch has few row blocks, so that more compute units work on the chunk, and when it has about as many as
+ * there are compute units, where the sweeps are levelled: the row blocks of a KV head are laid end to end
+ * and cut into runs of equal cost, one workgroup each, which leaves compute units to the decode branch.
+ * Piece c of a cut item leaves its partial result in piece region (first region of the item) + c.  A prefill
+ * workgroup runs the pieces [first piece of the workgroup, .. the one marked last].
  * Decode items come in workgroups of W = block_threads / 64 wave slots.  A sequence is cut into 1, 2,
  * 4 .. W splits, or a multiple of W when W splits of 1024 tokens cannot cover it; its splits hold the
  * same number of pages up to one.  Consecutive splits of one (sequence, KV head) in one workgroup are a
@@ -144,19 +172,36 @@ tc_status tc_kv_append(const tc_plan *plan, const tc_kv_pool *pool, const void *
  * tokens; Sec. 2.2 chunk + piggybacked decodes): out[t][h] = softmax_j(scale * q[t][h] . k_j) v_j
  * over j = 0..p of the row's sequence, read from the pool as it is when the kernel runs, so
  * tc_kv_append of the same batch must precede it on the same stream.  Prefill chunks and
- * decode tokens are processed by one kernel launch; sequences whose KV range was split get
- * their partial results combined by a small second launch.  fp32 accumulation; probabilities and
- * the output are rounded to nearest even in the element type.  scale must be positive and finite.  q, out, workspace: DEVICE.  Results are bitwise reproducible
- * for a fixed plan. */
+ * decode tokens are processed by ONE kernel launch.  Where a KV range was split (long decode
+ * sequences, cut prefill items) every part leaves an fp32 partial result in the workspace and counts
+ * its arrival; the part that arrives last combines them, in index order, so the result does not
+ * depend on which part that is.  No workgroup ever waits for another.  fp32 accumulation;
+ * probabilities and the output are rounded to nearest even in the element type.  scale must be
+ * positive and finite.  q, out, workspace: DEVICE.  Results are bitwise reproducible for a fixed
+ * plan.  Two calls that use the same plan (its arrival counters) or the same workspace must not
+ * overlap in time. */
 tc_status tc_mixed_attention(const tc_plan *plan, const tc_kv_pool *pool, const void *q, void *out, float scale,
                              void *workspace, size_t workspace_bytes, void *stream);
 
-/* The two launches of tc_mixed_attention, one per call, for callers that time them or put other
- * work between them (same operation, paper Sec. 2.1; same arguments, checks and errors).
- * tc_attention_partials runs the attention kernel: rows whose KV range is not split are final in
- * `out`, the others leave fp32 partial results in the workspace.  tc_split_merge combines those
- * partials into `out`; it launches nothing when the plan has no split range.  The pair, in this
- * order on one stream with the same out and workspace, is bit for bit tc_mixed_attention. */
+/* tc_kv_append and tc_mixed_attention of the same batch in one call (paper Sec. 2.1: the new tokens'
+ * K and V are cached as part of the iteration that computes them).  The new row of every decode
+ * sequence is stored into the pool by the one wavefront that runs the sequence's last KV split, before
+ * that wavefront fetches the page it lies in: no second launch touches it and no other wavefront reads it.  The
+ * rows of prefill chunks are read by many workgroups of the attention kernel, which may not wait for
+ * one another, so they are stored first by the append kernel, restricted to the chunks' rows: a batch
+ * of decodes is one launch, a mixed batch two.  Pools and outputs are bit for bit those of
+ * tc_kv_append followed by tc_mixed_attention. */
+tc_status tc_mixed_attention_append(const tc_plan *plan, const tc_kv_pool *pool, const void *q, const void *k_new,
+                                    const void *v_new, void *out, float scale, void *workspace, size_t workspace_bytes,
+                                    void *stream);
+
+/* The same operation (paper Sec. 2.1) with the combination of partial results as a launch of its
+ * own, for callers that time the parts or put other work between them (same arguments, checks and
+ * errors).  tc_attention_partials runs the attention kernel without the in-kernel combination: rows
+ * whose KV range is not split are final in `out`, the others leave fp32 partial results in the
+ * workspace.  tc_split_merge combines those partials into `out`; it launches nothing when the plan
+ * has no split range.  The pair, in this order on one stream with the same out and workspace, is
+ * bit for bit tc_mixed_attention. */
 tc_status tc_attention_partials(const tc_plan *plan, const tc_kv_pool *pool, const void *q, void *out, float scale,
                                 void *workspace, size_t workspace_bytes, void *stream);
 tc_status tc_split_merge(const tc_plan *plan, const tc_kv_pool *pool, void *out, void *workspace,
@@ -191,6 +236,16 @@ tc_status tc_kv_export(const tc_plan *plan, const tc_kv_pool *pool, int32_t seq,
                        const void *const *k_pools, const void *const *v_pools, void *buffer, void *stream);
 tc_status tc_kv_import(const tc_plan *plan, const tc_kv_pool *pool, int32_t seq, int32_t num_layers,
                        void *const *k_pools, void *const *v_pools, const void *buffer, void *stream);
+
+/* Measurement probes (no part of the method): two bare loops whose rate on the chip at hand is the
+ * practical ceiling the kernels above are compared with, next to the published peaks.  The caller times
+ * them with events on `stream`.
+ * tc_probe_mfma_loop: 256 workgroups of 8 wavefronts, each wavefront 4 * iters MFMA 32x32x16 bf16
+ * (32768 flop each) on independent accumulators; sink: DEVICE, at least 512 KiB, receives one float per thread.
+ * tc_probe_stream_read: reads `bytes` bytes of src (DEVICE, 16-byte aligned) once with non-temporal
+ * loads; sink: DEVICE, at least 4 bytes. */
+tc_status tc_probe_mfma_loop(int32_t iters, void *sink, size_t sink_bytes, void *stream);
+tc_status tc_probe_stream_read(const void *src, size_t bytes, void *sink, void *stream);
 
 const char *tc_status_str(tc_status s);
 /* Text of the last error raised on the calling thread ("" if none). */

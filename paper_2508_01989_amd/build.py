@@ -10,7 +10,7 @@ ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libtc_mi355x.so")
 SCHED_LIB = os.path.join(HERE, "libtc_sched.so")  # host-only scheduling core, built with the host compiler
-SOURCES = ["tc_plan.cpp", "tc_api.cpp", "tc_kernels.hip"]
+SOURCES = ["tc_plan.cpp", "tc_api.cpp", "tc_kernels.hip", "tc_probe.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared", "-fno-gpu-rdc",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
          "-Wall", "-Wno-unused-command-line-argument"]

@@ -22,16 +22,16 @@ tc_status check_runnable(const tc_plan *plan, const tc_kv_pool *pool) {
     return TC_OK;
 }
 
-tc_status attention(const tc_plan *plan, const tc_kv_pool *pool, const void *q, void *out, float scale, void *workspace,
-                    size_t workspace_bytes, int launches, void *stream, const char *what) {
+tc_status attention(const tc_plan *plan, const tc_kv_pool *pool, const void *q, const void *k_new, const void *v_new, void *out,
+                    float scale, void *workspace, size_t workspace_bytes, int launches, void *stream, const char *what) {
     tc_status st = check_runnable(plan, pool);
     if (st != TC_OK) return st;
     if (plan->T == 0) return TC_OK;
-    if (!out || (!q && (launches & tc::kLaunchAttention))) return fail(TC_ERR_NULL, "q or out is NULL");
+    if (!out || (!q && (launches & (tc::kLaunchAttention | tc::kLaunchFused)))) return fail(TC_ERR_NULL, "q or out is NULL");
     const size_t need = plan->workspace_bytes();
     if (need > 0 && (!workspace || workspace_bytes < need)) return fail(TC_ERR_WORKSPACE, "workspace missing or too small");
     if (!(scale > 0.f) || scale > 3.0e38f) return fail(TC_ERR_ARG, "scale must be positive and finite");
-    return device_result(tc::launch_attention(plan, pool, q, out, scale, need ? workspace : nullptr, launches, stream), what);
+    return device_result(tc::launch_attention(plan, pool, q, k_new, v_new, out, scale, need ? workspace : nullptr, launches, stream), what);
 }
 
 }  // namespace
@@ -43,24 +43,55 @@ tc_status tc_kv_append(const tc_plan *plan, const tc_kv_pool *pool, const void *
     if (st != TC_OK) return st;
     if (plan->T == 0) return TC_OK;
     if (!k_new || !v_new) return fail(TC_ERR_NULL, "k_new or v_new is NULL");
-    return device_result(tc::launch_kv_append(plan, pool, k_new, v_new, stream), "tc_kv_append launch");
+    return device_result(tc::launch_kv_append(plan, pool, k_new, v_new, false, stream), "tc_kv_append launch");
 }
 
 tc_status tc_mixed_attention(const tc_plan *plan, const tc_kv_pool *pool, const void *q, void *out, float scale,
                              void *workspace, size_t workspace_bytes, void *stream) {
-    return attention(plan, pool, q, out, scale, workspace, workspace_bytes, tc::kLaunchAttention | tc::kLaunchMerge, stream,
+    return attention(plan, pool, q, nullptr, nullptr, out, scale, workspace, workspace_bytes, tc::kLaunchFused, stream,
                      "tc_mixed_attention launch");
+}
+
+tc_status tc_mixed_attention_append(const tc_plan *plan, const tc_kv_pool *pool, const void *q, const void *k_new,
+                                    const void *v_new, void *out, float scale, void *workspace, size_t workspace_bytes,
+                                    void *stream) {
+    tc_status st = check_runnable(plan, pool);
+    if (st != TC_OK) return st;
+    if (plan->T == 0) return TC_OK;
+    if (!k_new || !v_new) return fail(TC_ERR_NULL, "k_new or v_new is NULL");
+    if (!out || !q) return fail(TC_ERR_NULL, "q or out is NULL");
+    const size_t need = plan->workspace_bytes();
+    if (need > 0 && (!workspace || workspace_bytes < need)) return fail(TC_ERR_WORKSPACE, "workspace missing or too small");
+    if (!(scale > 0.f) || scale > 3.0e38f) return fail(TC_ERR_ARG, "scale must be positive and finite");
+    // the rows of prefill chunks are read by many workgroups: they are stored first, by the append kernel
+    st = device_result(tc::launch_kv_append(plan, pool, k_new, v_new, true, stream), "tc_mixed_attention_append launch");
+    if (st != TC_OK) return st;
+    return device_result(tc::launch_attention(plan, pool, q, k_new, v_new, out, scale, need ? workspace : nullptr, tc::kLaunchFused, stream),
+                         "tc_mixed_attention_append launch");
 }
 
 tc_status tc_attention_partials(const tc_plan *plan, const tc_kv_pool *pool, const void *q, void *out, float scale,
                                 void *workspace, size_t workspace_bytes, void *stream) {
-    return attention(plan, pool, q, out, scale, workspace, workspace_bytes, tc::kLaunchAttention, stream,
+    return attention(plan, pool, q, nullptr, nullptr, out, scale, workspace, workspace_bytes, tc::kLaunchAttention, stream,
                      "tc_attention_partials launch");
 }
 
 tc_status tc_split_merge(const tc_plan *plan, const tc_kv_pool *pool, void *out, void *workspace, size_t workspace_bytes,
                          void *stream) {
-    return attention(plan, pool, nullptr, out, 1.f, workspace, workspace_bytes, tc::kLaunchMerge, stream, "tc_split_merge launch");
+    return attention(plan, pool, nullptr, nullptr, nullptr, out, 1.f, workspace, workspace_bytes, tc::kLaunchMerge, stream,
+                     "tc_split_merge launch");
+}
+
+tc_status tc_probe_mfma_loop(int32_t iters, void *sink, size_t sink_bytes, void *stream) {
+    if (!sink) return fail(TC_ERR_NULL, "sink is NULL");
+    if (iters < 1 || sink_bytes < (size_t)tc::kNumCu * 512 * sizeof(float)) return fail(TC_ERR_ARG, "iters < 1 or sink smaller than 512 KiB");
+    return device_result(tc::launch_probe_mfma(iters, sink, stream), "tc_probe_mfma_loop launch");
+}
+
+tc_status tc_probe_stream_read(const void *src, size_t bytes, void *sink, void *stream) {
+    if (!src || !sink) return fail(TC_ERR_NULL, "src or sink is NULL");
+    if (bytes < 16) return fail(TC_ERR_ARG, "nothing to read");
+    return device_result(tc::launch_probe_stream(src, bytes, sink, stream), "tc_probe_stream_read launch");
 }
 
 tc_status tc_kv_gather(const tc_plan *plan, const tc_kv_pool *pool, int32_t seq, void *k_out, void *v_out, void *stream) {

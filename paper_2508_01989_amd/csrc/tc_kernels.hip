@@ -25,13 +25,11 @@
 #include <hip/hip_runtime.h>
 
 #include <algorithm>
+#include <atomic>
+#include <cstdlib>
 #include <type_traits>
 
 #include "tc_internal.h"
-
-#ifndef TC_PREFILL_STAGES
-#define TC_PREFILL_STAGES 3
-#endif
 
 namespace tc {
 
@@ -69,16 +67,24 @@ typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 
 struct AttnArgs {
-    const uint16_t *k_pool, *v_pool, *q;
+    uint16_t *k_pool, *v_pool;  // written only by the variant that also stores the batch's new rows
+    const uint16_t *q;
+    const uint16_t *k_new, *v_new;  // this iteration's K/V rows, or null when tc_kv_append has stored them already
     uint16_t *out;
     const int32_t *pages;    // page ids of all sequences, CSR by sequence
     const int32_t *prefill;  // work items
-    const int32_t *pieces;   // one per prefill workgroup: item and KV tile range
+    const int32_t *pieces;   // KV tile ranges of prefill items, stored workgroup by workgroup
+    const int32_t *wg_first; // first piece of every prefill workgroup
     const int32_t *decode;
+    const int32_t *merge;    // merge items: where the partial results of a split pair lie
+    int32_t *counters;       // arrival counters of split pairs; zero before and after every launch
     float *ws_o;             // [n_partials][G][D]
     float *ws_ml;            // [n_partials][G][2]  (running max in the log2 domain, running sum)
-    int n_prefill, n_decode;
+    float *ws_pieces;        // piece regions of cut prefill items (PiecePartial), behind the decode partials
+    int n_prefill, n_decode; // prefill workgroups, decode wave slots
     int Hq, Hkv, G;
+    int fused;               // 1: the last piece or team of a split pair to finish combines its partial results
+    int queue;               // index of the decode queue's two counters (next unit, workgroups that have left), or -1
     float scale_log2;        // softmax scale times log2(e)
 };
 
@@ -243,6 +249,215 @@ __global__ void __launch_bounds__(256) kv_migrate_kernel(const MigratePools pool
 }
 
 // ------------------------------------------------------------------------------------
+// Combination of partial results
+// ------------------------------------------------------------------------------------
+// Partial results that are combined inside the attention kernel cross from one compute unit to another
+// (possibly on another die, with an L2 cache of its own) while the kernel runs.  They are written and read
+// with device-scope atomic stores and loads (relaxed; 8 bytes each), which go past the caches that are not
+// coherent across the device, so no cache has to be written back or invalidated as a whole: a release
+// and an acquire fence per piece (an L2 write-back and an L2 invalidate, by every wave) measured twice
+// the kernel time on a levelled 2048-token chunk.  Ordering is by the arrival counter: a writer waits
+// until its stores have completed (s_waitcnt) before it counts itself in; the reader is the part that sees
+// the full count.  PEER = false: the plain loads of the merge launch, which runs after the kernel has ended.
+__device__ __forceinline__ void peer_store2(float *p, float a, float b) {
+    const uint64_t bits = (uint64_t)__float_as_uint(a) | ((uint64_t)__float_as_uint(b) << 32);
+    __hip_atomic_store(reinterpret_cast<uint64_t *>(p), bits, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+template <bool PEER>
+__device__ __forceinline__ float2 load2(const float *p) {
+    if (!PEER) return *reinterpret_cast<const float2 *>(p);
+    const uint64_t bits = __hip_atomic_load(reinterpret_cast<const uint64_t *>(p), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    return float2{__uint_as_float((uint32_t)bits), __uint_as_float((uint32_t)(bits >> 32))};
+}
+template <bool PEER>
+__device__ __forceinline__ float load1(const float *p) {
+    if (!PEER) return *p;
+    return __uint_as_float(__hip_atomic_load(reinterpret_cast<const uint32_t *>(p), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT));
+}
+__device__ __forceinline__ void stores_done() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); }
+
+// One output row (query head j of a decode sequence, or of one position of a cut prefill item) from its
+// ns partial results in workspace slots slot0 .. slot0 + ns - 1:
+//   out = sum_i 2^(m_i - m*) o_i / sum_i 2^(m_i - m*) l_i,   m* = max_i m_i,   partials in index order.
+// One wavefront per row; a lane owns D/64 adjacent head-dim elements, so each partial row is one coalesced
+// read.  Lane i first fetches (m_i, l_i) of partial i (at most 64 per pass; passes are chained by an online
+// rescale), the wave reduces the maximum, and the weighted sum runs over the partials in index order with
+// the weights broadcast from those registers.  The order is fixed, so the result does not depend on which
+// workgroup runs this or when.
+template <int D, class E, bool PEER>
+__device__ __forceinline__ void merge_row(const float *ws_o, const float *ws_ml, int64_t slot0, int ns, int G, int j,
+                                          uint16_t *dst_row, int lane) {
+    constexpr int NE = D / 64;  // elements per lane
+    float acc[NE];
+#pragma unroll
+    for (int e = 0; e < NE; e++) acc[e] = 0.f;
+    float m_star = -1e30f, den = 0.f;
+    for (int base = 0; base < ns; base += 64) {
+        const int n = min(64, ns - base);
+        const float *src = ws_o + ((int64_t)(slot0 + base) * G + j) * D + lane * NE;
+        // Partial rows are fetched kChunk at a time, all loads of a chunk in flight together; the
+        // first chunk is requested before the weights are known.
+        constexpr int kChunk = 8;
+        float row[kChunk][NE];
+        auto fetch = [&](int c0) {
+#pragma unroll
+            for (int u = 0; u < kChunk; u++)
+                if (c0 + u < n) {
+                    const float *r = src + (int64_t)(c0 + u) * G * D;
+                    if (NE == 2) {
+                        const float2 v = load2<PEER>(r);
+                        row[u][0] = v.x;
+                        row[u][NE - 1] = v.y;
+                    } else {
+                        row[u][0] = load1<PEER>(r);
+                    }
+                }
+        };
+        fetch(0);
+        const int64_t my_row = (int64_t)(slot0 + base + min(lane, n - 1)) * G + j;
+        const float2 ml = load2<PEER>(ws_ml + my_row * 2);  // lanes past n read the last partial's pair and ignore it
+        const float m_i = lane < n ? ml.x : -1e30f;
+        const float l_i = lane < n ? ml.y : 0.f;
+        float m_new = m_i;
+#pragma unroll
+        for (int sh = 1; sh < 64; sh *= 2) m_new = fmaxf(m_new, xor_lanes(m_new, sh));
+        m_new = fmaxf(m_new, m_star);
+        const float rescale = fast_exp2(m_star - m_new);
+        m_star = m_new;
+        const float w_i = fast_exp2(m_i - m_star);  // 0 for lanes past n
+        float wl = w_i * l_i;
+#pragma unroll
+        for (int sh = 1; sh < 64; sh *= 2) wl += xor_lanes(wl, sh);
+        den = den * rescale + wl;
+#pragma unroll
+        for (int e = 0; e < NE; e++) acc[e] *= rescale;
+        for (int c0 = 0; c0 < n; c0 += kChunk) {
+#pragma unroll
+            for (int u = 0; u < kChunk; u++)
+                if (c0 + u < n) {
+                    const float w = __shfl(w_i, c0 + u, 64);
+#pragma unroll
+                    for (int e = 0; e < NE; e++) acc[e] += w * row[u][e];
+                }
+            if (c0 + kChunk < n) fetch(c0 + kChunk);
+        }
+    }
+    const float inv = 1.f / den;
+    uint16_t *dst = dst_row + lane * NE;
+    if (NE == 2) {
+        typename E::x2 w2;
+        w2[0] = (typename E::t)(acc[0] * inv);
+        w2[1] = (typename E::t)(acc[NE - 1] * inv);
+        *reinterpret_cast<typename E::x2 *>(dst) = w2;
+    } else {
+        const typename E::t w1 = (typename E::t)(acc[0] * inv);
+        *dst = __builtin_bit_cast(uint16_t, w1);
+    }
+}
+
+// Arrival of one of the n parts of a split pair, after the part has stored its partial result with
+// peer_store2 and the stores have completed: the pair's counter is incremented.  Returns true to the part
+// that arrives last; that part combines the partial results (reading them with PEER loads) and puts the
+// counter back to zero for the next launch.  Nobody waits for anybody.
+// `leader`: the one lane that does the counting; all lanes of the calling wave get its answer.
+__device__ __forceinline__ bool arrive_is_last(int32_t *counter, int n, bool leader) {
+    stores_done();
+    int old = 0;
+    if (leader) old = __hip_atomic_fetch_add(counter, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    old = __builtin_amdgcn_readfirstlane(old);
+    return old == n - 1;
+}
+
+// Partial result of one piece of a cut prefill item: what the 512 lanes of the workgroup hold at the end of
+// the piece's sweep, stored as it lies in registers.  Lane (wave, n = lane % 32, hh = lane / 32) owns row
+// wave * 32 + n and, of its D accumulators, those at head-dim positions 32 c + 8 q + 4 hh .. + 3 (c < D/32, q < 4).
+//   o:  [wave][chunk = 4 c + q][lane][4] floats   one store instruction of a wave = 1 KiB contiguous
+//   ml: [wave][n][2] floats                         (running maximum in the log2 domain, row sum)
+// The combination reads the K partial results of an item back in the same layout, so it needs no exchange
+// between lanes and all its loads are independent:
+//   o = sum_i 2^(m_i - m*) o_i,  l = sum_i 2^(m_i - m*) l_i,  m* = max_i m_i,  pieces in index order,
+// which leaves the lane with the accumulators and row sum of the whole item, as after an uncut sweep.
+template <int D>
+struct PiecePartial {
+    static constexpr int MT = D / 32;
+    static constexpr int kChunks = 4 * MT;
+    static constexpr int kOFloats = kMixedWaves * kChunks * 64 * 4;  // = kPrefillRows * D
+    static constexpr int kFloats = kOFloats + kPrefillRows * 2;
+    static __device__ __forceinline__ void store(float *region, int wave, int lane, const f32x16 (&o)[MT], float m, float l, bool peer) {
+        float *dst = region + ((int64_t)wave * kChunks * 64 + lane) * 4;
+        float *ml = region + kOFloats + (wave * 32 + (lane & 31)) * 2;
+        if (peer) {
+#pragma unroll
+            for (int c = 0; c < MT; c++)
+#pragma unroll
+                for (int q = 0; q < 4; q++) {
+                    peer_store2(dst + (4 * c + q) * 256, o[c][4 * q], o[c][4 * q + 1]);
+                    peer_store2(dst + (4 * c + q) * 256 + 2, o[c][4 * q + 2], o[c][4 * q + 3]);
+                }
+            if (lane < 32) peer_store2(ml, m, l);
+        } else {
+#pragma unroll
+            for (int c = 0; c < MT; c++)
+#pragma unroll
+                for (int q = 0; q < 4; q++)
+                    __builtin_nontemporal_store(f32x4{o[c][4 * q], o[c][4 * q + 1], o[c][4 * q + 2], o[c][4 * q + 3]},
+                                                reinterpret_cast<f32x4 *>(dst + (4 * c + q) * 256));
+            if (lane < 32) {
+                ml[0] = m;
+                ml[1] = l;
+            }
+        }
+    }
+    // `first`: region of the item's piece 0; the K regions follow each other.
+    template <bool PEER>
+    static __device__ __forceinline__ void combine(const float *first, int k, int wave, int lane, f32x16 (&o)[MT], float &l) {
+        const float *ml = first + kOFloats + (wave * 32 + (lane & 31)) * 2;
+        float m_star = -1e30f;
+        for (int i = 0; i < k; i++) m_star = fmaxf(m_star, load2<PEER>(ml + (int64_t)i * kFloats).x);
+#pragma unroll
+        for (int c = 0; c < MT; c++)
+#pragma unroll
+            for (int r = 0; r < 16; r++) o[c][r] = 0.f;
+        l = 0.f;
+        for (int i = 0; i < k; i++) {
+            const float *src = first + (int64_t)i * kFloats + ((int64_t)wave * kChunks * 64 + lane) * 4;
+            const float2 mli = load2<PEER>(ml + (int64_t)i * kFloats);
+            f32x16 t[MT];
+#pragma unroll
+            for (int c = 0; c < MT; c++)
+#pragma unroll
+                for (int q = 0; q < 4; q++) {
+                    const float2 a = load2<PEER>(src + (4 * c + q) * 256), b = load2<PEER>(src + (4 * c + q) * 256 + 2);
+                    t[c][4 * q] = a.x; t[c][4 * q + 1] = a.y; t[c][4 * q + 2] = b.x; t[c][4 * q + 3] = b.y;
+                }
+            const float w = fast_exp2(mli.x - m_star);
+            l += w * mli.y;
+#pragma unroll
+            for (int c = 0; c < MT; c++)
+#pragma unroll
+                for (int r = 0; r < 16; r++) o[c][r] += w * t[c][r];
+        }
+    }
+};
+
+// Output rows of a prefill item from a lane's accumulators and its row's sum: o / l, rounded to the element type.
+template <int D, class E>
+__device__ __forceinline__ void prefill_write_rows(uint16_t *row, const f32x16 (&o)[D / 32], float l, int hh) {
+    typedef typename E::x4 x4;
+    typedef typename E::t el;
+    const float inv = 1.f / l;
+#pragma unroll
+    for (int c = 0; c < D / 32; c++)
+#pragma unroll
+        for (int q4 = 0; q4 < 4; q4++) {
+            x4 w;
+#pragma unroll
+            for (int e = 0; e < 4; e++) w[e] = (el)(o[c][4 * q4 + e] * inv);
+            *reinterpret_cast<x4 *>(row + 32 * c + 8 * q4 + 4 * hh) = w;
+        }
+}
+
+// ------------------------------------------------------------------------------------
 // Prefill branch: one workgroup = 256 (position, head) rows of one KV head, 32 per wave.
 // ------------------------------------------------------------------------------------
 // Row R of the workgroup is position first_pos + R / G, query head kv_head * G + R % G.
@@ -260,11 +475,13 @@ struct PrefillCfg {
     static constexpr int kTileBytes = kTilePages * kPageBytes;      // K part or V part of one LDS stage
     static constexpr int kRuns = kPageBytes / 1024;                 // 1 KiB wave-wide loads per page and tensor
     // kStages LDS stages of K and of V: a tile is copied kStages - 1 steps before its first use.
-    // 96 KiB at D = 128 with three stages, 128 KiB with four.
-    static constexpr int kStages = TC_PREFILL_STAGES;
-    static_assert(kStages == 3 || kStages == 4, "the page-id pipeline below is written for 3 or 4 stages");
+    // 96 KiB at D = 128.  (A fourth stage, 128 KiB, measured no faster; the pipeline below is written in
+    // terms of kStages, but three is the only depth that is built and tested.)
+    static constexpr int kStages = 3;
+    static_assert(kStages == 3, "three stages is the only depth that is built and tested");
     static constexpr int kIdSlots = kStages - 2;  // page ids in flight per copying wave and tensor
-    static constexpr int kLdsBytes = 2 * kStages * kTileBytes + kMixedWaves * kIdSlots * 64 * 4;
+    static constexpr int kQueueSlot = 2 * kStages * kTileBytes + kMixedWaves * kIdSlots * 64 * 4;  // where a workgroup keeps the decode unit it drew
+    static constexpr int kLdsBytes = kQueueSlot + 16;
 };
 
 // N direct-to-LDS loads of 1 KiB each (16 bytes per lane) at immediate offsets 0, 1024, ...
@@ -475,12 +692,16 @@ __device__ void prefill_item(const AttnArgs &A, const int32_t *__restrict__ it, 
     using C = PrefillCfg<D>;
     using W = PrefillWave<D, E>;
     using x8 = typename E::x8;
-    using x4 = typename E::x4;
     using el = typename E::t;
     typedef typename W::lds_cptr lds_cptr;
     constexpr int KS = W::KS, MT = W::MT;
-    const int lane = threadIdx.x & 63;
-    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    // A workgroup may run several pieces in a loop.  Everything a lane derives from its index is derived again
+    // for every piece (the empty asm hides that the index does not change): hoisted out of that loop, the
+    // values only the start of a piece needs would occupy registers throughout the sweep, which has none to spare.
+    int tid = threadIdx.x;
+    asm volatile("" : "+v"(tid));
+    const int lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int n = lane & 31, hh = lane >> 5;
     const int kvh = it[PF_KVH], pos0 = it[PF_POS0], npos = it[PF_NPOS], qrow0 = it[PF_QROW0], ctx = it[PF_CTX];
     const int n_pages = it[PF_NPAGES];
@@ -674,36 +895,27 @@ __device__ void prefill_item(const AttnArgs &A, const int32_t *__restrict__ it, 
     // the product of the last half
     W::pv(vf, pb, o);
 
-    const float l = half_swap_sum(l_run);
-    if (!row_valid) return;
+    float l = half_swap_sum(l_run);
     if (p_slot >= 0) {
-        // A piece of a cut item: unnormalised accumulators, running maximum (log2 domain) and row sum
-        // go to the workspace, in the partial layout the decode splits use; rows that see no key of
-        // this piece carry (m, l, o) = (-1e30, 0, 0) and get weight 0 in the merge.
-        const int64_t prow = ((int64_t)(p_slot + (Rc / G) * p_k)) * G + Rc % G;
-        float *dst = A.ws_o + prow * D + 4 * hh;
-#pragma unroll
-        for (int c = 0; c < MT; c++)
-#pragma unroll
-            for (int q4 = 0; q4 < 4; q4++)
-                __builtin_nontemporal_store(f32x4{o[c][4 * q4], o[c][4 * q4 + 1], o[c][4 * q4 + 2], o[c][4 * q4 + 3]},
-                                            reinterpret_cast<f32x4 *>(dst + 32 * c + 8 * q4));
-        if (hh == 0) {
-            A.ws_ml[prow * 2] = m_run;
-            A.ws_ml[prow * 2 + 1] = l;
-        }
-    } else {
-        const float inv = 1.f / l;
-#pragma unroll
-        for (int c = 0; c < MT; c++)
-#pragma unroll
-            for (int q4 = 0; q4 < 4; q4++) {
-                x4 w;
-#pragma unroll
-                for (int e = 0; e < 4; e++) w[e] = (el)(o[c][4 * q4 + e] * inv);
-                *reinterpret_cast<x4 *>(A.out + row_off + 32 * c + 8 * q4 + 4 * hh) = w;
-            }
+        // A piece of a cut item: every lane leaves its unnormalised accumulators, and the rows' running maximum
+        // (log2 domain) and sum, in the piece's region of the workspace as they lie in registers; rows that see no
+        // key of this piece carry (m, l, o) = (-1e30, 0, 0) and get weight 0 in the combination.
+        float *const region = A.ws_pieces + (int64_t)(p_slot + pc[PP_C]) * PiecePartial<D>::kFloats;
+        PiecePartial<D>::store(region, wave, lane, o, m_run, l, A.fused != 0);
+        if (!A.fused) return;
+        // The last of the item's pieces to get here combines them all (the others leave; nobody waits).  Every
+        // wave waits for its own stores to complete, the workgroup meets, one thread counts the arrival.
+        stores_done();
+        __syncthreads();  // every wave has left the sweep: LDS is free
+        int *const arrived = reinterpret_cast<int *>(lds);
+        int32_t *const counter = A.counters + pc[PP_COUNTER];
+        if (tid == 0) *arrived = __hip_atomic_fetch_add(counter, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        __syncthreads();
+        if (*arrived != p_k - 1) return;
+        if (tid == 0) __hip_atomic_store(counter, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);  // for the next launch
+        PiecePartial<D>::template combine<true>(A.ws_pieces + (int64_t)p_slot * PiecePartial<D>::kFloats, p_k, wave, lane, o, l);
     }
+    if (row_valid) prefill_write_rows<D, E>(A.out + row_off, o, l, hh);
 }
 
 // ------------------------------------------------------------------------------------
@@ -714,10 +926,12 @@ __device__ void prefill_item(const AttnArgs &A, const int32_t *__restrict__ it, 
 //   S^T[token][head] = sum_d K[token][d] Q[head][d]   16x16x32, D/32 steps; lane gets tokens 4g..4g+3
 //   O^T[d][head]    += sum_token V^T[d][token] P^T[token][head]   16x16x16, contraction over the page's
 //                      16 tokens: lane feeds tokens 4g..4g+3
-// Pages resident in registers per wave: one being consumed, the rest in flight.  Two keep the
-// decode-only kernel within 168 VGPRs (three waves per SIMD; a third stage spills there); three or four
-// measured the same bandwidth in the eight-wave shape of a launch with a prefill chunk.
+// Pages resident in registers per wave (NS): one being consumed, the rest in flight.  Two keep the
+// decode-only kernel within 168 VGPRs (three waves per SIMD; a third stage spills there).  In a launch
+// with a prefill chunk the decode workgroups are one per compute unit and share the chip with the chunk, so
+// a few units must carry the whole decode stream: there a wave keeps kMixedDecodeStages - 1 pages in flight.
 constexpr int kDecodeStages = 2;
+constexpr int kMixedDecodeStages = 4;
 
 template <int D>
 struct DecodePage {  // K and V of one page, in MFMA A-operand registers
@@ -726,6 +940,30 @@ struct DecodePage {  // K and V of one page, in MFMA A-operand registers
 };
 
 // KV pages are read exactly once per launch, by one wavefront: stream them past the caches.
+// When the attention kernel also does the append, the newest token of a decode sequence (index tn of the
+// last page of its last KV split, pool block `id`) is stored into the pool by the wavefront that runs that
+// split, before the wavefront fetches the page: the lane that stores a piece is the lane that reads it back
+// (same (token, piece) and (element, token group) ownership as in decode_fetch), the store is complete
+// before the fetch is issued, and no other wavefront reads or writes that slot, so nothing else has to be ordered.
+template <int D>
+__device__ __forceinline__ void decode_store_new_token(const AttnArgs &A, int kvh, int id, int qrow, int tn, int j, int g) {
+    const int64_t tile_elems = (int64_t)kBlock * D;
+    uint16_t *kb = A.k_pool + ((int64_t)id * A.Hkv + kvh) * tile_elems;
+    uint16_t *vb = A.v_pool + ((int64_t)id * A.Hkv + kvh) * tile_elems;
+    const uint16_t *kn = A.k_new + ((int64_t)qrow * A.Hkv + kvh) * D;
+    const uint16_t *vn = A.v_new + ((int64_t)qrow * A.Hkv + kvh) * D;
+    if (j == tn) {  // K: the 8-element pieces 4 kk + g of token j
+#pragma unroll
+        for (int kk = 0; kk < D / 32; kk++)
+            *reinterpret_cast<u32x4 *>(kb + ((4 * kk + g) * kBlock + tn) * 8) = *reinterpret_cast<const u32x4 *>(kn + (4 * kk + g) * 8);
+    }
+    if (g == (tn >> 2)) {  // V: tokens 4 g .. 4 g + 3 of the elements 16 c + j
+#pragma unroll
+        for (int c = 0; c < D / 16; c++) vb[(16 * c + j) * kBlock + v_slot(tn)] = vn[16 * c + j];
+    }
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+}
+
 template <int D>
 __device__ __forceinline__ void decode_fetch(const AttnArgs &A, int kvh, int id, int j, int g, DecodePage<D> &st) {
     const int64_t tile_elems = (int64_t)kBlock * D;
@@ -792,19 +1030,22 @@ __device__ __forceinline__ void decode_consume(const AttnArgs &A, DecodePage<D> 
 // Bytes of LDS a decode workgroup of `waves` waves needs for that.
 __host__ __device__ constexpr size_t decode_team_lds_bytes(int waves, int G, int D) { return (size_t)waves * G * (D + 2) * sizeof(float); }
 
-template <int D, class E>
+template <int D, class E, int NS>
 __device__ void decode_item(const AttnArgs &A, const int32_t *__restrict__ it, float *team_lds, int wg_waves) {
     using x8 = typename E::x8;
     using x4 = typename E::x4;
     using el = typename E::t;
     constexpr int KS = D / 32;  // k-steps of K Q^T
     constexpr int MT = D / 16;  // 16-row tiles of O^T
-    constexpr int NS = kDecodeStages;
-    const int lane = threadIdx.x & 63;
-    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    int tid = threadIdx.x;
+    asm volatile("" : "+v"(tid));  // may be called in a loop: derive the per-lane values afresh for every item (see prefill_item)
+    const int lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int j = lane & 15, g = lane >> 4;
     const int kvh = it[DC_KVH], t0 = it[DC_BEGIN], t1 = it[DC_END], qrow = it[DC_QROW], slot = it[DC_SLOT];
-    const int team_n = it[DC_TEAM] & 0xff, team_pos = it[DC_TEAM] >> 8;
+    const int team_n = it[DC_TEAM] & 15, team_pos = (it[DC_TEAM] >> 4) & 7, merge_item = (it[DC_TEAM] >> 8) - 1;
+    // the split ends with the sequence's newest token and this launch is the one that stores it
+    const bool takes_new = (it[DC_TEAM] & kTeamTailBit) && A.k_new != nullptr;
     const int G = A.G;
     const int n_tok = t1 - t0;  // 0: a padding item, which only takes part in the barrier
 
@@ -817,6 +1058,7 @@ __device__ void decode_item(const AttnArgs &A, const int32_t *__restrict__ it, f
         const int page0 = t0 / kBlock;
         const int n_pg = (n_tok + kBlock - 1) / kBlock;  // 1..64
         const int32_t *pages = A.pages + it[DC_PAGEOFF] + page0;
+        if (takes_new) decode_store_new_token<D>(A, kvh, pages[n_pg - 1], qrow, (n_tok - 1) & (kBlock - 1), j, g);
         const int my_page = pages[min(lane, n_pg - 1)];  // lane i holds the id of page i of the split
 
         x8 qreg[KS];
@@ -875,184 +1117,253 @@ __device__ void decode_item(const AttnArgs &A, const int32_t *__restrict__ it, f
             my_ml[2 * j + 1] = l_run;
         }
     }
-    __syncthreads();  // executed once by every wave of a decode workgroup
-    if (team_pos > 0 || n_tok == 0 || j >= G) return;
+    __syncthreads();  // executed once by every wave of a decode workgroup, for every unit of items it runs
+    if (team_pos > 0 || n_tok == 0) return;
+    const int jc = min(j, G - 1);  // head columns past G are padding: they follow column G - 1 and store nothing
     for (int i = 1; i < team_n; i++) {
-        const float m_i = my_ml[(i * G + j) * 2], l_i = my_ml[(i * G + j) * 2 + 1];
+        const float m_i = my_ml[(i * G + jc) * 2], l_i = my_ml[(i * G + jc) * 2 + 1];
         const float m_new = fmaxf(m_run, m_i);
         const float a = fast_exp2(m_run - m_new), b = fast_exp2(m_i - m_new);
         m_run = m_new;
         l_run = l_run * a + l_i * b;
-        const float *src = my_o + (size_t)i * G * D + j * D + 4 * g;
+        const float *src = my_o + (size_t)i * G * D + jc * D + 4 * g;
 #pragma unroll
         for (int c = 0; c < MT; c++) o[c] = o[c] * a + *reinterpret_cast<const f32x4 *>(src + 16 * c) * b;
     }
     if (slot < 0) {
-        const float inv = 1.f / l_run;
-        uint16_t *dst = A.out + ((int64_t)qrow * A.Hq + kvh * G + j) * D + 4 * g;
+        if (j < G) {
+            const float inv = 1.f / l_run;
+            uint16_t *dst = A.out + ((int64_t)qrow * A.Hq + kvh * G + j) * D + 4 * g;
 #pragma unroll
-        for (int c = 0; c < MT; c++) {
-            x4 w;
+            for (int c = 0; c < MT; c++) {
+                x4 w;
 #pragma unroll
-            for (int e = 0; e < 4; e++) w[e] = (el)(o[c][e] * inv);
-            *reinterpret_cast<x4 *>(dst + 16 * c) = w;
+                for (int e = 0; e < 4; e++) w[e] = (el)(o[c][e] * inv);
+                *reinterpret_cast<x4 *>(dst + 16 * c) = w;
+            }
         }
-    } else {
-        // partial results are written once and read once, by the merge: stream them past the caches (plain
-        // stores of these 2 KiB per split measured 3 % less bandwidth on a batch of decodes)
+        return;
+    }
+    if (j < G) {
         float *dst = A.ws_o + ((int64_t)slot * G + j) * D + 4 * g;
+        float *ml = A.ws_ml + ((int64_t)slot * G + j) * 2;
+        if (A.fused) {
 #pragma unroll
-        for (int c = 0; c < MT; c++) __builtin_nontemporal_store(o[c], reinterpret_cast<f32x4 *>(dst + 16 * c));
-        if (g == 0) {
-            float *ml = A.ws_ml + ((int64_t)slot * G + j) * 2;
-            ml[0] = m_run;
-            ml[1] = l_run;
+            for (int c = 0; c < MT; c++) {
+                peer_store2(dst + 16 * c, o[c][0], o[c][1]);
+                peer_store2(dst + 16 * c + 2, o[c][2], o[c][3]);
+            }
+            if (g == 0) peer_store2(ml, m_run, l_run);
+        } else {
+            // partial results are written once and read once: stream them past the caches (plain
+            // stores of these 2 KiB per split measured 3 % less bandwidth on a batch of decodes)
+#pragma unroll
+            for (int c = 0; c < MT; c++) __builtin_nontemporal_store(o[c], reinterpret_cast<f32x4 *>(dst + 16 * c));
+            if (g == 0) {
+                ml[0] = m_run;
+                ml[1] = l_run;
+            }
         }
     }
+    if (!A.fused) return;
+    // the last team of the (sequence, KV head) to get here combines the partial results of all of them
+    const int32_t *mg = A.merge + (int64_t)merge_item * kItemInts;
+    int32_t *const counter = A.counters + mg[MG_COUNTER];
+    if (!arrive_is_last(counter, mg[MG_NSPLIT], lane == 0)) return;
+    for (int h = 0; h < G; h++)
+        merge_row<D, E, true>(A.ws_o, A.ws_ml, mg[MG_SLOT0], mg[MG_NSPLIT], G, h, A.out + ((int64_t)qrow * A.Hq + kvh * G + h) * D, lane);
+    if (lane == 0) __hip_atomic_store(counter, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
 
 struct AttnScalars {
     int n_prefill, n_decode;
     int Hq, Hkv, G;
+    int fused;
+    int queue;
+    int n_partials;
     float scale_log2;
 };
 
-// The pointers are separate __restrict__ kernel arguments (not struct members) so that the
-// compiler knows the work list and the page table are never written and can fetch them with
+// The work lists and the page table are separate const __restrict__ kernel arguments (not struct
+// members) so that the compiler knows they are never written and can fetch them with
 // scalar loads.  WAVES = 8: batches with a prefill chunk (one workgroup per compute unit, up to 256
 // registers per wave); WAVES = 4: decode-only batches (three workgroups per compute unit).
+// Workgroups [0, n_prefill) run the prefill pieces the plan gave them, one after the other; the rest run
+// decode items, one per wave.
 template <int D, class E, int WAVES>
 __global__ void __launch_bounds__(WAVES * 64, WAVES == kMixedWaves ? 1 : kDecodeWgPerCu)
-    mixed_attention_kernel(const uint16_t *__restrict__ k_pool, const uint16_t *__restrict__ v_pool,
-                           const uint16_t *__restrict__ q, uint16_t *__restrict__ out, const int32_t *__restrict__ pages,
+    mixed_attention_kernel(uint16_t *k_pool, uint16_t *v_pool, const uint16_t *__restrict__ q, const uint16_t *__restrict__ k_new,
+                           const uint16_t *__restrict__ v_new, uint16_t *__restrict__ out, const int32_t *__restrict__ pages,
                            const int32_t *__restrict__ prefill, const int32_t *__restrict__ pieces,
-                           const int32_t *__restrict__ decode, float *__restrict__ ws_o, float *__restrict__ ws_ml,
-                           const AttnScalars sc) {
+                           const int32_t *__restrict__ wg_first, const int32_t *__restrict__ decode,
+                           const int32_t *__restrict__ merge, int32_t *counters, float *ws, const AttnScalars sc) {
     extern __shared__ __align__(16) char lds[];
     AttnArgs A;
-    A.k_pool = k_pool; A.v_pool = v_pool; A.q = q; A.out = out; A.pages = pages; A.prefill = prefill; A.pieces = pieces; A.decode = decode;
-    A.ws_o = ws_o; A.ws_ml = ws_ml;
-    A.n_prefill = sc.n_prefill; A.n_decode = sc.n_decode; A.Hq = sc.Hq; A.Hkv = sc.Hkv; A.G = sc.G;
+    A.k_pool = k_pool; A.v_pool = v_pool; A.q = q; A.k_new = k_new; A.v_new = v_new; A.out = out; A.pages = pages; A.prefill = prefill;
+    A.pieces = pieces; A.wg_first = wg_first; A.decode = decode; A.merge = merge; A.counters = counters;
+    // workspace: decode partials [n_partials][G][D], their (max, sum) pairs [n_partials][G][2], then the piece regions
+    A.ws_o = ws; A.ws_ml = ws + (int64_t)sc.n_partials * sc.G * D; A.ws_pieces = A.ws_ml + (int64_t)sc.n_partials * sc.G * 2;
+    A.n_prefill = sc.n_prefill; A.n_decode = sc.n_decode; A.Hq = sc.Hq; A.Hkv = sc.Hkv; A.G = sc.G; A.fused = sc.fused; A.queue = sc.queue;
     A.scale_log2 = sc.scale_log2;
+    constexpr int NS = WAVES == kMixedWaves ? kMixedDecodeStages : kDecodeStages;
     if (WAVES == kMixedWaves && (int)blockIdx.x < A.n_prefill) {
         if constexpr (WAVES == kMixedWaves) {
-            const int32_t *pc = pieces + (int64_t)blockIdx.x * kItemInts;
-            prefill_item<D, E>(A, prefill + (int64_t)pc[PP_ITEM] * kItemInts, pc, lds);
+            const int32_t *pc = pieces + (int64_t)wg_first[blockIdx.x] * kItemInts;
+            for (;;) {
+                prefill_item<D, E>(A, prefill + (int64_t)pc[PP_ITEM] * kItemInts, pc, lds);
+                if (pc[PP_LAST]) break;
+                pc += kItemInts;
+                __syncthreads();  // the next piece's tile copies reuse the LDS
+            }
         }
-    } else {
+    } else if (WAVES != kMixedWaves || A.queue < 0) {
         const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
         const int idx = ((int)blockIdx.x - A.n_prefill) * WAVES + wave;
         // the decode items fill whole workgroups (padding items at the end of some): every wave gets one
-        if (idx < A.n_decode) decode_item<D, E>(A, decode + (int64_t)idx * kItemInts, reinterpret_cast<float *>(lds), WAVES);
+        if (idx < A.n_decode) decode_item<D, E, NS>(A, decode + (int64_t)idx * kItemInts, reinterpret_cast<float *>(lds), WAVES);
+    }
+    if constexpr (WAVES == kMixedWaves) {
+        if (A.queue < 0) return;
+        // Decode queue (the launch has no more workgroups than the chip has compute units, all resident from the
+        // start).  The decode items are handed out in units of one workgroup's worth (WAVES items, teams included)
+        // through a counter: the workgroups launched for the decode branch draw from the start, the prefill
+        // workgroups join when their pieces are done, and everybody leaves when the counter has passed the last unit,
+        // so that whichever compute unit is free carries the decode stream and no workgroup waits for another.
+        // (Left to the hardware, decode workgroups beyond the first round were not started on the units the first
+        // round had freed until the prefill workgroups ended.  Handing out single items to single waves, with the
+        // splits of a pair combined by the last to arrive, measured slower than units with their teams.)
+        // The workgroup that leaves last puts both counters back to zero for the next launch.
+        int *const drawn = reinterpret_cast<int *>(lds + PrefillCfg<D>::kQueueSlot);
+        int32_t *const next_unit = A.counters + A.queue, *const gone = next_unit + 1;
+        const int n_units = A.n_decode / WAVES;
+        const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+        for (;;) {
+            __syncthreads();  // the unit before (or the last prefill piece) is done with the LDS
+            if (threadIdx.x == 0) *drawn = __hip_atomic_fetch_add(next_unit, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            __syncthreads();
+            const int unit = *drawn;
+            if (unit >= n_units) break;
+            decode_item<D, E, NS>(A, decode + ((int64_t)unit * WAVES + wave) * kItemInts, reinterpret_cast<float *>(lds), WAVES);
+        }
+        if (threadIdx.x == 0 && __hip_atomic_fetch_add(gone, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == (int)gridDim.x - 1) {
+            __hip_atomic_store(next_unit, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            __hip_atomic_store(gone, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        }
     }
 }
 
 // ------------------------------------------------------------------------------------
-// Split-KV merge: out = sum_i 2^(m_i - m*) o_i / sum_i 2^(m_i - m*) l_i, splits in index order.
-// One workgroup per (sequence, KV head); one wavefront per query head; a lane owns D/64 adjacent
-// head-dim elements, so each partial row is one coalesced read.  Lane i first fetches (m_i, l_i) of
-// split i (at most 64 splits per wave pass), the wave reduces the maximum, and the weighted sum runs
-// over the splits, in index order, with the weights broadcast from those registers.
+// Split-KV merge as a launch of its own (the two-call form; the fused kernel does the same inside)
+// ------------------------------------------------------------------------------------
+// One workgroup per split decode (sequence, KV head) pair; one wavefront per query head.
 template <int D, class E>
 __global__ void __launch_bounds__(256) split_merge_kernel(const int32_t *__restrict__ items, const float *__restrict__ ws_o,
                                                           const float *__restrict__ ws_ml, uint16_t *__restrict__ out,
                                                           int Hq, int G) {
-    constexpr int NE = D / 64;  // elements per lane
     const int32_t *it = items + (int64_t)blockIdx.x * kItemInts;
-    const int kvh = it[MG_KVH], qrow = it[MG_QROW], slot0 = it[MG_SLOT0], ns = it[MG_NSPLIT];
+    const int kvh = it[MG_KVH], qrow = it[MG_QROW], ns = it[MG_NSPLIT], slot0 = it[MG_SLOT0];
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    for (int j = wave; j < G; j += 4) {
-        float acc[NE];
-#pragma unroll
-        for (int e = 0; e < NE; e++) acc[e] = 0.f;
-        float m_star = -1e30f, den = 0.f;
-        for (int base = 0; base < ns; base += 64) {  // 64 splits per pass; passes chained by an online rescale
-            const int n = min(64, ns - base);
-            const float *src = ws_o + ((int64_t)(slot0 + base) * G + j) * D + lane * NE;
-            // Partial rows are fetched kChunk at a time, all loads of a chunk in flight together; the
-            // first chunk is requested before the weights are known.
-            constexpr int kChunk = 8;
-            float row[kChunk][NE];
-            auto fetch = [&](int c0) {
-#pragma unroll
-                for (int u = 0; u < kChunk; u++)
-                    if (c0 + u < n) {
-                        const float *r = src + (int64_t)(c0 + u) * G * D;
-                        if (NE == 2) {
-                            const float2 v = *reinterpret_cast<const float2 *>(r);
-                            row[u][0] = v.x;
-                            row[u][NE - 1] = v.y;
-                        } else {
-                            row[u][0] = r[0];
-                        }
-                    }
-            };
-            fetch(0);
-            const int64_t my_row = (int64_t)(slot0 + base + min(lane, n - 1)) * G + j;
-            const float m_i = lane < n ? ws_ml[my_row * 2] : -1e30f;
-            const float l_i = lane < n ? ws_ml[my_row * 2 + 1] : 0.f;
-            float m_new = m_i;
-#pragma unroll
-            for (int sh = 1; sh < 64; sh *= 2) m_new = fmaxf(m_new, xor_lanes(m_new, sh));
-            m_new = fmaxf(m_new, m_star);
-            const float rescale = fast_exp2(m_star - m_new);
-            m_star = m_new;
-            const float w_i = fast_exp2(m_i - m_star);  // 0 for lanes past n
-            float wl = w_i * l_i;
-#pragma unroll
-            for (int sh = 1; sh < 64; sh *= 2) wl += xor_lanes(wl, sh);
-            den = den * rescale + wl;
-#pragma unroll
-            for (int e = 0; e < NE; e++) acc[e] *= rescale;
-            for (int c0 = 0; c0 < n; c0 += kChunk) {
-#pragma unroll
-                for (int u = 0; u < kChunk; u++)
-                    if (c0 + u < n) {
-                        const float w = __shfl(w_i, c0 + u, 64);
-#pragma unroll
-                        for (int e = 0; e < NE; e++) acc[e] += w * row[u][e];
-                    }
-                if (c0 + kChunk < n) fetch(c0 + kChunk);
-            }
-        }
-        const float inv = 1.f / den;
-        uint16_t *dst = out + ((int64_t)qrow * Hq + kvh * G + j) * D + lane * NE;
-        if (NE == 2) {
-            typename E::x2 w2;
-            w2[0] = (typename E::t)(acc[0] * inv);
-            w2[1] = (typename E::t)(acc[NE - 1] * inv);
-            *reinterpret_cast<typename E::x2 *>(dst) = w2;
-        } else {
-            const typename E::t w1 = (typename E::t)(acc[0] * inv);
-            *dst = __builtin_bit_cast(uint16_t, w1);
-        }
+    for (int j = wave; j < G; j += 4) merge_row<D, E, false>(ws_o, ws_ml, slot0, ns, G, j, out + ((int64_t)qrow * Hq + kvh * G + j) * D, lane);
+}
+
+// One workgroup per cut prefill item, with the lane-to-row map of the prefill branch: the lanes read the pieces'
+// partial results back as the pieces' lanes left them and write the item's output rows.
+template <int D, class E>
+__global__ void __launch_bounds__(kMixedWaves * 64) prefill_merge_kernel(const int32_t *__restrict__ items, const int32_t *__restrict__ prefill,
+                                                                          const float *__restrict__ ws_pieces, uint16_t *__restrict__ out,
+                                                                          int Hq, int G) {
+    const int32_t *mg = items + (int64_t)blockIdx.x * kItemInts;
+    const int32_t *it = prefill + (int64_t)mg[MG_ITEM] * kItemInts;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, n = lane & 31, hh = lane >> 5;
+    const int kvh = it[PF_KVH], pos0 = it[PF_POS0], npos = it[PF_NPOS], qrow0 = it[PF_QROW0];
+    const int R = wave * 32 + n;
+    f32x16 o[D / 32];
+    float l;
+    PiecePartial<D>::template combine<false>(ws_pieces + (int64_t)mg[MG_SLOT0] * PiecePartial<D>::kFloats, mg[MG_NSPLIT], wave, lane, o, l);
+    if (R < npos * G) prefill_write_rows<D, E>(out + ((int64_t)(qrow0 + pos0 + R / G) * Hq + kvh * G + R % G) * D, o, l, hh);
+}
+
+// ------------------------------------------------------------------------------------
+// Plan buffers
+// ------------------------------------------------------------------------------------
+const char *hip_error_text(int err) { return hipGetErrorString((hipError_t)err); }
+
+int begin_plan_host(tc_plan *p, size_t n) {
+    if (p->upload_event) {
+        hipError_t e = hipEventSynchronize((hipEvent_t)p->upload_event);
+        if (e != hipSuccess) return (int)e;
     }
+    if (n <= p->host_cap) return 0;
+    const size_t cap = std::max<size_t>(n + n / 2, 4096);
+    int32_t *fresh = nullptr;
+    if (p->on_device) {
+        hipError_t e = hipHostMalloc((void **)&fresh, cap * sizeof(int32_t), hipHostMallocDefault);
+        if (e != hipSuccess) return (int)e;
+    } else {
+        fresh = (int32_t *)std::malloc(cap * sizeof(int32_t));
+        if (!fresh) return (int)hipErrorOutOfMemory;
+    }
+    if (p->host) {
+        if (p->host_pinned) (void)hipHostFree(p->host); else std::free(p->host);
+    }
+    p->host = fresh;
+    p->host_cap = cap;
+    p->host_pinned = p->on_device;
+    return 0;
+}
+
+// Copy the host image to the device on `stream`.  The device buffer grows when a work list is larger than
+// any before it and is otherwise reused: a serving loop that keeps one plan object allocates nothing per
+// iteration.  (Growing frees the old buffer, which waits for the device to finish whatever still reads it.)
+int upload_plan(tc_plan *p, void *stream) {
+    int device = -1;
+    hipError_t e = hipGetDevice(&device);
+    if (e != hipSuccess) return (int)e;
+    if (p->device >= 0 && p->device != device) return (int)hipErrorInvalidDevice;
+    p->device = device;
+    if (p->host_n > p->dev_cap) {
+        if (p->dev) (void)hipFree(p->dev);
+        p->dev = nullptr;
+        p->dev_cap = 0;
+        e = hipMalloc((void **)&p->dev, p->host_cap * sizeof(int32_t));
+        if (e != hipSuccess) { p->dev = nullptr; return (int)e; }
+        p->dev_cap = p->host_cap;
+    }
+    if (!p->upload_event) {
+        hipEvent_t ev;
+        e = hipEventCreateWithFlags(&ev, hipEventDisableTiming);
+        if (e != hipSuccess) return (int)e;
+        p->upload_event = ev;
+    }
+    e = hipMemcpyAsync(p->dev, p->host, p->host_n * sizeof(int32_t), hipMemcpyHostToDevice, (hipStream_t)stream);
+    if (e != hipSuccess) return (int)e;
+    return (int)hipEventRecord((hipEvent_t)p->upload_event, (hipStream_t)stream);
+}
+
+void free_plan_buffers(tc_plan *p) {
+    if (p->upload_event) {
+        (void)hipEventSynchronize((hipEvent_t)p->upload_event);
+        (void)hipEventDestroy((hipEvent_t)p->upload_event);
+        p->upload_event = nullptr;
+    }
+    if (p->dev) (void)hipFree(p->dev);
+    p->dev = nullptr;
+    p->dev_cap = 0;
+    if (p->host) {
+        if (p->host_pinned) (void)hipHostFree(p->host); else std::free(p->host);
+    }
+    p->host = nullptr;
+    p->host_cap = p->host_n = 0;
 }
 
 // ------------------------------------------------------------------------------------
 // Launchers
 // ------------------------------------------------------------------------------------
-const char *hip_error_text(int err) { return hipGetErrorString((hipError_t)err); }
-
-int upload_plan(tc_plan *p, void *stream) {
-    hipError_t e = hipGetDevice(&p->device);
-    if (e != hipSuccess) return (int)e;
-    const size_t bytes = p->host.size() * sizeof(int32_t);
-    e = hipMalloc((void **)&p->dev, bytes);
-    if (e != hipSuccess) { p->dev = nullptr; return (int)e; }
-    e = hipMemcpyAsync(p->dev, p->host.data(), bytes, hipMemcpyHostToDevice, (hipStream_t)stream);
-    return (int)e;
-}
-
-void free_plan_device(tc_plan *p) {
-    if (p->dev) (void)hipFree(p->dev);
-    p->dev = nullptr;
-}
-
-int launch_kv_append(const tc_plan *p, const tc_kv_pool *pool, const void *k_new, const void *v_new, void *stream) {
-    if (p->n_append == 0) return 0;
+int launch_kv_append(const tc_plan *p, const tc_kv_pool *pool, const void *k_new, const void *v_new, bool only_prefill, void *stream) {
+    const int n = only_prefill ? p->n_append_prefill : p->n_append;
+    if (n == 0) return 0;
     hipStream_t st = (hipStream_t)stream;
-    const dim3 grid((unsigned)p->n_append, (unsigned)p->Hkv);  // Hkv <= 1024 is checked when the plan is built
+    const dim3 grid((unsigned)n, (unsigned)p->Hkv);  // Hkv <= 1024 is checked when the plan is built
     if (p->D == 128)
         kv_append_kernel<128><<<grid, 512, 0, st>>>((uint16_t *)pool->k_pool, (uint16_t *)pool->v_pool, (const uint16_t *)k_new,
                                                    (const uint16_t *)v_new, p->dev + p->off_append, p->Hkv);
@@ -1103,51 +1414,76 @@ int launch_kv_migrate(const tc_plan *p, bool import, int page0, int n_pages, int
     return 0;
 }
 
+// More than 64 KiB of dynamic LDS needs an opt-in per kernel function and per device; remembered per
+// instantiation and device (setting it twice is harmless, so racing first calls need no lock).
+template <int D, class E>
+static int allow_prefill_lds(int device) {
+    static std::atomic<bool> done[kMaxDevices];
+    const bool known = device >= 0 && device < kMaxDevices;
+    if (known && done[device].load(std::memory_order_acquire)) return 0;
+    hipError_t e = hipFuncSetAttribute((const void *)mixed_attention_kernel<D, E, kMixedWaves>,
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, PrefillCfg<D>::kLdsBytes);
+    if (e != hipSuccess) return (int)e;
+    if (known) done[device].store(true, std::memory_order_release);
+    return 0;
+}
+
 template <int D, class E>
 static int launch_attention_d(const tc_plan *p, const AttnArgs &A, int launches, hipStream_t st) {
-    const int grid = (launches & kLaunchAttention) ? p->grid_blocks() : 0;
-    const AttnScalars sc = {A.n_prefill, A.n_decode, A.Hq, A.Hkv, A.G, A.scale_log2};
+    const int grid = (launches & (kLaunchAttention | kLaunchFused)) ? p->grid_blocks() : 0;
+    const AttnScalars sc = {A.n_prefill, A.n_decode, A.Hq, A.Hkv, A.G, A.fused, A.queue, p->n_partials, A.scale_log2};
     if (grid > 0 && p->n_pieces > 0) {
-        static bool lds_ok = false;  // opt in to more than 64 KiB of dynamic LDS once per process
         const int lds = PrefillCfg<D>::kLdsBytes;  // the decode workgroups of the launch need less, for any G
         static_assert(decode_team_lds_bytes(kMixedWaves, 16, D) <= (size_t)PrefillCfg<D>::kLdsBytes, "team buffers must fit the prefill tiles' LDS");
-        if (!lds_ok) {
-            hipError_t e = hipFuncSetAttribute((const void *)mixed_attention_kernel<D, E, kMixedWaves>,
-                                               hipFuncAttributeMaxDynamicSharedMemorySize, lds);
-            if (e != hipSuccess) return (int)e;
-            lds_ok = true;
-        }
-        mixed_attention_kernel<D, E, kMixedWaves><<<grid, kMixedWaves * 64, lds, st>>>(A.k_pool, A.v_pool, A.q, A.out, A.pages, A.prefill,
-                                                                                   A.pieces, A.decode, A.ws_o, A.ws_ml, sc);
+        if (int err = allow_prefill_lds<D, E>(p->device)) return err;
+        mixed_attention_kernel<D, E, kMixedWaves><<<grid, kMixedWaves * 64, lds, st>>>(
+            A.k_pool, A.v_pool, A.q, A.k_new, A.v_new, A.out, A.pages, A.prefill, A.pieces, A.wg_first, A.decode, A.merge, A.counters,
+            A.ws_o, sc);
     } else if (grid > 0) {
-        mixed_attention_kernel<D, E, kDecodeWaves><<<grid, kDecodeWaves * 64, decode_team_lds_bytes(kDecodeWaves, p->G, D), st>>>(A.k_pool, A.v_pool, A.q, A.out, A.pages, A.prefill,
-                                                                                   A.pieces, A.decode, A.ws_o, A.ws_ml, sc);
+        mixed_attention_kernel<D, E, kDecodeWaves><<<grid, kDecodeWaves * 64, decode_team_lds_bytes(kDecodeWaves, p->G, D), st>>>(
+            A.k_pool, A.v_pool, A.q, A.k_new, A.v_new, A.out, A.pages, A.prefill, A.pieces, A.wg_first, A.decode, A.merge, A.counters,
+            A.ws_o, sc);
     }
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return (int)e;
-    if ((launches & kLaunchMerge) && p->n_merge > 0)
-        split_merge_kernel<D, E><<<p->n_merge, 256, 0, st>>>(p->dev + p->off_merge, A.ws_o, A.ws_ml, A.out, A.Hq, A.G);
+    if ((launches & kLaunchMerge) && p->n_merge_prefill > 0) {
+        prefill_merge_kernel<D, E><<<p->n_merge_prefill, kMixedWaves * 64, 0, st>>>(p->dev + p->off_merge, p->dev + p->off_prefill, A.ws_pieces,
+                                                                                    A.out, A.Hq, A.G);
+        e = hipGetLastError();
+        if (e != hipSuccess) return (int)e;
+    }
+    if ((launches & kLaunchMerge) && p->n_merge > p->n_merge_prefill)
+        split_merge_kernel<D, E><<<p->n_merge - p->n_merge_prefill, 256, 0, st>>>(p->dev + p->off_merge + (size_t)p->n_merge_prefill * kItemInts,
+                                                                                 A.ws_o, A.ws_ml, A.out, A.Hq, A.G);
     return (int)hipGetLastError();
 }
 
-int launch_attention(const tc_plan *p, const tc_kv_pool *pool, const void *q, void *out, float scale, void *workspace,
-                     int launches, void *stream) {
+int launch_attention(const tc_plan *p, const tc_kv_pool *pool, const void *q, const void *k_new, const void *v_new, void *out,
+                     float scale, void *workspace, int launches, void *stream) {
     AttnArgs A;
-    A.k_pool = (const uint16_t *)pool->k_pool;
-    A.v_pool = (const uint16_t *)pool->v_pool;
+    A.k_pool = (uint16_t *)pool->k_pool;
+    A.v_pool = (uint16_t *)pool->v_pool;
     A.q = (const uint16_t *)q;
+    A.k_new = (const uint16_t *)k_new;
+    A.v_new = (const uint16_t *)v_new;
     A.out = (uint16_t *)out;
     A.pages = p->dev + p->off_pages;
     A.prefill = p->dev + p->off_prefill;
     A.pieces = p->dev + p->off_pieces;
+    A.wg_first = p->dev + p->off_wg;
     A.decode = p->dev + p->off_decode;
+    A.merge = p->dev + p->off_merge;
+    A.counters = p->dev + p->off_counters;
     A.ws_o = (float *)workspace;
     A.ws_ml = A.ws_o ? A.ws_o + (size_t)p->n_partials * p->G * p->D : nullptr;
-    A.n_prefill = p->n_pieces;  // workgroups of the prefill branch
+    A.ws_pieces = A.ws_o ? A.ws_ml + (size_t)p->n_partials * p->G * 2 : nullptr;
+    A.n_prefill = p->n_prefill_wg;
     A.n_decode = p->n_decode;
     A.Hq = p->Hq;
     A.Hkv = p->Hkv;
     A.G = p->G;
+    A.fused = (launches & kLaunchFused) ? 1 : 0;
+    A.queue = p->queue_counter;
     A.scale_log2 = scale * 1.4426950408889634f;
     hipStream_t st = (hipStream_t)stream;
     if (p->dtype == TC_FP16) return p->D == 128 ? launch_attention_d<128, Fp16>(p, A, launches, st) : launch_attention_d<64, Fp16>(p, A, launches, st);

@@ -155,9 +155,11 @@ def check_work_list(tc, sp, table, nb):
     cost = pf[:, 5] + pf[:, 2] + pf[:, 3]
     assert np.all(np.diff(cost[::Hkv]) <= 0) and np.all(pf[:, 1] == np.arange(len(pf)) % Hkv)
     # pieces: the 64-token KV tiles of every item are covered once, by 1 piece (writes out) or by k pieces
-    # (partial slots), most tiles first
+    # (piece regions slot0 + c, one arrival counter per cut item)
     assert len(pc) == info.num_prefill_pieces
     slots = []
+    regions = []
+    counters = []
     merge_expected = []
     for i, item in enumerate(pf):
         mine = pc[pc[:, 0] == i]
@@ -166,25 +168,47 @@ def check_work_list(tc, sp, table, nb):
         k = len(mine)
         assert mine[0, 1] == 0 and mine[-1, 2] == n_tiles and np.all(mine[1:, 1] == mine[:-1, 2])
         assert np.all(mine[:, 2] > mine[:, 1]) and np.all(mine[:, 4] == k)
+        assert mine[:, 5].tolist() == list(range(k))
         if k == 1:
-            assert mine[0, 3] == -1
+            assert mine[0, 3] == -1 and mine[0, 6] == -1
         else:
             base = int(mine[0, 3])
-            assert mine[:, 3].tolist() == [base + c for c in range(k)]
-            for pos in range(int(item[3])):
-                slots += [base + pos * k + c for c in range(k)]
-                merge_expected.append((int(item[0]), int(item[1]), int(item[4] + item[2] + pos), base + pos * k, k))
-    # order: most tiles first
-    size = pc[:, 2] - pc[:, 1]
-    assert np.all(np.diff(size) <= 0)
-    if 256 % Hkv == 0:  # the KV head stays the fastest index: workgroup id mod Hkv names it
-        assert np.all(pf[pc[:, 0], 1] == np.arange(len(pc)) % Hkv)
+            assert np.all(mine[:, 3] == base) and np.all(mine[:, 6] == mine[0, 6]) and mine[0, 6] >= 0
+            counters.append(int(mine[0, 6]))
+            regions += [base + c for c in range(k)]
+            merge_expected.append((int(item[0]), int(item[1]), int(item[4] + item[2]), base, k, int(mine[0, 6]), int(item[3]), i))
+    # prefill workgroups: each runs a run of consecutive pieces, the last one marked; together they hold every piece once
+    wg = p.items(4)
+    n_wg = info.num_prefill_workgroups
+    assert len(wg) == n_wg and (n_wg > 0) == (len(pc) > 0)
+    if n_wg:
+        assert wg[0] == 0 and np.all(np.diff(wg) > 0)
+        ends = np.flatnonzero(pc[:, 7] == 1)
+        assert np.array_equal(ends, np.append(wg[1:], len(pc)) - 1) and set(np.unique(pc[:, 7])) <= {0, 1}
+        # one KV head per workgroup; with a KV-head count that divides the compute units, workgroup id mod Hkv names it
+        wg_of_piece = np.searchsorted(wg, np.arange(len(pc)), side="right") - 1
+        heads = pf[pc[:, 0], 1]
+        for w_ in range(n_wg):
+            assert len(set(heads[wg_of_piece == w_])) == 1
+        if 256 % Hkv == 0:
+            assert np.all(heads == wg_of_piece % Hkv)
+        tiles_of_wg = np.bincount(wg_of_piece, weights=(pc[:, 2] - pc[:, 1]), minlength=n_wg)
+        levelled = 256 < 4 * len(pf) <= 16 * 256 and len(pc) > len(pf)
+        if not levelled:      # one piece per workgroup, most tiles first (uncut items, or few items whose KV ranges are cut)
+            assert n_wg == len(pc) and np.all(np.diff(tiles_of_wg[::Hkv]) <= 0)
+        else:                 # about as many items as compute units and little decode work: every KV head has the same runs, of nearly equal cost (tiles + 3 per piece)
+            assert n_wg % Hkv == 0 and n_wg <= 256
+            cost_of_wg = tiles_of_wg + 3 * np.bincount(wg_of_piece, minlength=n_wg)
+            per_head = cost_of_wg.reshape(-1, Hkv)
+            assert np.all(per_head == per_head[:, :1])
+            assert per_head[:, 0].max() <= per_head[:, 0].mean() * 1.15 + 8
     # decode: the items fill whole workgroups of W waves; padding items hold no tokens
     W_ = info.block_threads // 64
     assert len(dc) % W_ == 0 and len(dc) == info.num_decode_items
     real = dc[dc[:, 3] > dc[:, 2]]
     pad = dc[dc[:, 3] == dc[:, 2]]
     assert np.all(pad[:, 0] == -1) and np.all(pad[:, 7] == 1) and len(pad) < 32 * W_
+    team_n, team_pos, tail, merge_idx = dc[:, 7] & 15, (dc[:, 7] >> 4) & 7, (dc[:, 7] >> 7) & 1, (dc[:, 7] >> 8) - 1
     # splits tile [0, kv_len) page-aligned, <= 64 pages each, for every KV head
     for s in np.flatnonzero(sp.q_len == 1):
         for h in range(Hkv):
@@ -194,7 +218,9 @@ def check_work_list(tc, sp, table, nb):
             assert np.all(it[:, 2] % 16 == 0) and np.all(it[:, 3] - it[:, 2] <= 1024)
             assert np.all(it[:, 4] == qs[s])
             # 1, 2, 4 .. W splits (one team), or a multiple of W when W splits of 1024 tokens cannot cover the sequence
-            n_teams = int(np.sum(it[:, 7] >> 8 == 0))
+            n_teams = int(np.sum((it[:, 7] >> 4) & 7 == 0))
+            # exactly the split that ends the sequence is marked as holding the newest token
+            assert np.array_equal((it[:, 7] >> 7) & 1, (it[:, 3] == sp.kv_len[s]).astype(int))
             assert len(it) in (1, 2, 4, 8)[:W_.bit_length()] if sp.kv_len[s] <= W_ * 1024 else len(it) % W_ == 0
             assert n_teams == -(-len(it) // W_)
             # a partial slot exactly when the splits are in more than one team (then one slot per team)
@@ -203,10 +229,11 @@ def check_work_list(tc, sp, table, nb):
     i = 0
     leaders = []
     while i < len(dc):
-        n, pos = int(dc[i, 7]) & 0xFF, int(dc[i, 7]) >> 8
+        n, pos = int(team_n[i]), int(team_pos[i])
         assert pos == 0 and 1 <= n <= W_ and i // W_ == (i + n - 1) // W_
         team = dc[i:i + n]
-        assert np.all(team[:, 7] == n + 256 * np.arange(n))
+        assert np.all(team_n[i:i + n] == n) and np.array_equal(team_pos[i:i + n], np.arange(n))
+        assert np.all(merge_idx[i:i + n] == merge_idx[i])
         if team[0, 3] > team[0, 2]:
             assert np.all(team[:, 0] == team[0, 0]) and np.all(team[:, 1] == team[0, 1]) and np.all(team[:, 5] == team[0, 5])
             assert np.all(team[1:, 2] == team[:-1, 3])
@@ -215,19 +242,36 @@ def check_work_list(tc, sp, table, nb):
             assert n == 1
         i += n
     leaders = np.array(leaders).reshape(-1, 8)
-    # partial slots: unique and dense over decode teams and prefill pieces together
+    # partial slots of decode teams and piece regions of cut prefill items: each unique and dense
     slots += leaders[leaders[:, 5] >= 0, 5].tolist()
     assert len(slots) == info.num_partials and sorted(slots) == list(range(info.num_partials))
-    # merge items name exactly the slots of their teams / pieces
+    assert len(regions) == info.num_piece_partials and sorted(regions) == list(range(info.num_piece_partials))
+    # merge items name exactly the slots of their teams / pieces, and every team points at its pair's merge item
     for s in np.flatnonzero(sp.q_len == 1):
         for h in range(Hkv):
             mine = leaders[(leaders[:, 0] == s) & (leaders[:, 1] == h)]
+            m_idx = (mine[:, 7] >> 8) - 1
             if len(mine) > 1:
-                merge_expected.append((int(s), h, int(qs[s]), int(mine[:, 5].min()), len(mine)))
+                assert np.all(m_idx == m_idx[0]) and m_idx[0] >= 0
+                item = mg[m_idx[0]]
+                assert (item[0], item[1], item[2], item[3], item[4]) == (s, h, qs[s], mine[:, 5].min(), len(mine))
+                counters.append(int(item[5]))
+                merge_expected.append((int(s), h, int(qs[s]), int(mine[:, 5].min()), len(mine), int(item[5]), 1, -1))
                 assert sorted(mine[:, 5].tolist()) == list(range(mine[:, 5].min(), mine[:, 5].min() + len(mine)))
-    assert sorted(merge_expected) == sorted(tuple(int(x) for x in m[:5]) for m in mg)
-    assert p.workspace_bytes == info.num_partials * G * (sp.head_dim + 2) * 4
-    assert info.grid_blocks == info.num_prefill_pieces + -(-info.num_decode_items // (info.block_threads // 64))
+            else:
+                assert np.all(m_idx == -1)
+    assert sorted(merge_expected) == sorted(tuple(int(x) for x in m[:8]) for m in mg)
+    n_cut = sum(1 for m in mg if m[7] >= 0)
+    assert all(m[7] >= 0 for m in mg[:n_cut]) and all(m[7] < 0 for m in mg[n_cut:])   # those of cut prefill items come first
+    # arrival counters: one per split pair, dense
+    assert info.num_counters == len(counters) and sorted(counters) == list(range(len(counters)))
+    assert p.workspace_bytes == (info.num_partials * G + info.num_piece_partials * 256) * (sp.head_dim + 2) * 4
+    units = -(-info.num_decode_items // (info.block_threads // 64))
+    if info.decode_queue:   # no more workgroups than compute units; the decode items are drawn from a queue
+        assert 0 < info.num_prefill_workgroups <= 256 and units > 0
+        assert info.grid_blocks == info.num_prefill_workgroups + min(units, 256 - info.num_prefill_workgroups) <= 256
+    else:
+        assert info.grid_blocks == info.num_prefill_workgroups + units
     return info
 
 
@@ -236,7 +280,16 @@ def test_work_list_covers_the_batch_exactly(tc, idx):
     sp = W.config_spec(idx)
     table, mb, nb = W.make_tables(sp, np.random.default_rng(3))
     info = check_work_list(tc, sp, table, nb)
-    assert info.num_prefill_pieces == info.num_prefill_items  # these batches are not cut
+    if idx == 1:
+        # 256 row blocks for 256 compute units and about as much decode work as their uneven sweeps leave idle time:
+        # one uncut row block per workgroup, the decode items drawn from the queue by the workgroups that finish early
+        assert info.num_prefill_workgroups == info.num_prefill_pieces == info.num_prefill_items == 256
+        assert info.decode_queue == 1 and info.grid_blocks == 256 and info.num_piece_partials == 0
+    elif idx == 2:
+        # 32 row blocks beside a long decode phase: neither cut nor levelled
+        assert info.num_prefill_pieces == info.num_prefill_items == info.num_prefill_workgroups
+    else:
+        assert info.num_prefill_pieces == info.num_prefill_items == info.num_prefill_workgroups
 
 
 @pytest.mark.parametrize("name,Hq,Hkv,q_len,ctx,cut", [
@@ -245,6 +298,8 @@ def test_work_list_covers_the_batch_exactly(tc, idx):
     ("ragged chunk, G=5", 10, 2, [77, 1], [1500, 40], True),
     ("small chunk under a long decode phase", 32, 8, [128] + [1] * 256, [2048] + [3000] * 256, False),
     ("short context", 32, 8, [128], [100], False),
+    ("large chunk alone: levelled", 32, 8, [2048], [4096], True),
+    ("large chunk, few decodes: levelled, decode queue", 32, 8, [2048] + [1] * 4, [4096] + [500] * 4, True),
 ])
 def test_small_prefill_batches_are_cut_into_kv_pieces(tc, name, Hq, Hkv, q_len, ctx, cut):
     sp = W.custom_spec(name, Hq, Hkv, 128, q_len, ctx)
@@ -269,3 +324,33 @@ def test_work_list_invariants_on_random_batches(tc, seed):
     sp = W.custom_spec(f"rand{seed}", Hkv * G, Hkv, int(rng.choice([64, 128])), [q_len[i] for i in order], [ctx[i] for i in order])
     table, mb, nb = W.make_tables(sp, rng)
     check_work_list(tc, sp, table, nb)
+
+
+def test_plan_update_gives_the_work_lists_of_fresh_plans(tc):
+    """Two successive batches through one plan object (tc_plan_update) give the same work lists as fresh plans,
+    whatever was planned before; a failed update leaves an empty plan."""
+    shapes = [(32, 8, [2048] + [1] * 64, [4096] + [900] * 64), (32, 8, [1] * 40, [3000] * 40), (32, 8, [256, 1], [100, 70000]),
+              (32, 8, [5], [0])]
+    pool = tc.make_pool(32, 8, 128, 1 << 16)
+    reused = None
+    for Hq, Hkv, q_len, ctx in shapes + shapes[::-1]:
+        sp = W.custom_spec("u", Hq, Hkv, 128, q_len, ctx, num_blocks=1 << 16)
+        table, mb, nb = W.make_tables(sp, np.random.default_rng(len(q_len)))
+        qs = np.zeros(len(q_len) + 1, np.int32)
+        qs[1:] = np.cumsum(q_len)
+        fresh = tc.Plan(pool, qs, sp.ctx_len, table, host_only=True)
+        if reused is None:
+            reused = tc.Plan(pool, qs, sp.ctx_len, table, host_only=True)
+        else:
+            reused.update(pool, qs, sp.ctx_len, table)
+        for f in ("num_seqs", "total_q", "num_prefill_items", "num_decode_items", "num_merge_items", "num_partials", "split_tokens",
+                  "grid_blocks", "block_threads", "total_pages", "num_prefill_pieces", "num_prefill_workgroups", "num_counters", "num_piece_partials",
+                  "decode_queue"):
+            assert getattr(fresh.info, f) == getattr(reused.info, f), f
+        for kind in range(5):
+            assert np.array_equal(fresh.items(kind), reused.items(kind)), kind
+        assert fresh.workspace_bytes == reused.workspace_bytes
+    with pytest.raises(tc.TcError) as e:
+        reused.update(pool, np.array([0, 0], np.int32), np.zeros(1, np.int32), np.zeros((1, 1), np.int32))
+    assert e.value.status == tc.TC_ERR_SPAN
+    assert reused.info.num_seqs == 0 and reused.info.grid_blocks == 0 and reused.workspace_bytes == 0

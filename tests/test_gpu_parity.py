@@ -121,6 +121,12 @@ SMALL = {
     "cut_g1_head_dim_64": (4, 4, 64, [100, 1], [900, 30]),
     "cut_eight_pieces": (32, 8, 128, [64], [5000]),
     "cut_chunk_at_unaligned_offset": (16, 4, 128, [50, 1], [1111, 700]),
+    # about as many row blocks as compute units: alone (or with little decode work) their sweeps are levelled over
+    # workgroups that run several pieces and combine them in the kernel; beside enough decode work the row blocks run
+    # uncut and the decode items are drawn from a queue (single splits, and sequences of several splits)
+    "levelled_chunk_alone": (32, 8, 128, [700], [900]),
+    "levelled_chunk_few_decodes": (16, 4, 128, [1100, 1, 1], [300, 2500, 31]),
+    "queue_chunk_and_decodes": (32, 8, 128, [520] + [1] * 24, [200] + [1500, 40, 2100, 900, 3300, 64] * 4),
 }
 
 
@@ -130,7 +136,8 @@ def test_small_cases_match_oracle(H, name):
     b = W.make_batch(W.custom_spec(name, Hq, Hkv, D, q_len, ctx, seed=zlib.crc32(name.encode()) % 10007))
     _, db = run_and_compare(H, b, name)
     cut = db.plan.info.num_prefill_pieces > db.plan.info.num_prefill_items
-    assert cut or not name.startswith("cut_")
+    assert cut or not (name.startswith("cut_") or name.startswith("levelled_"))
+    assert db.plan.info.decode_queue or not name.startswith("queue_")
 
 
 def random_mix(seed):
@@ -319,6 +326,84 @@ def test_two_launch_form_equals_the_single_call(H):
     with pytest.raises(tc.TcError) as e:
         tc.tc_split_merge(db.plan, db.pool, None, db.workspace, db.plan.workspace_bytes)
     assert e.value.status == tc.TC_ERR_NULL
+
+
+FUSED_CASES = ["levelled_chunk_few_decodes", "queue_chunk_and_decodes", "decode_page_boundaries", "decode_split_boundaries", "decode_long_ragged", "decode_more_than_64_partials",
+               "teams_g16_with_prefill", "teams_d64_ragged", "two_prefill_segments_and_decodes", "gqa_g5", "head_dim_64",
+               "several_row_blocks_mid_context", "cut_small_chunk_long_context", "decode_single_token_context"]
+
+
+def check_fused_step(H, b, tag):
+    """tc_mixed_attention_append against tc_kv_append + tc_mixed_attention on the same batch: pools and outputs
+    bit for bit (the oracle comparison of the two-call form then covers the fused one)."""
+    print(f"[fused] {tag}", flush=True)
+    two = H.DeviceBatch(b)
+    two.step()
+    one = H.DeviceBatch(b)
+    one.step_fused()
+    k2, v2 = two.pools_host()
+    k1, v1 = one.pools_host()
+    assert np.array_equal(k1, k2) and np.array_equal(v1, v2), f"{tag}: pools differ"
+    assert np.array_equal(H.to_host(one.out), H.to_host(two.out)), f"{tag}: outputs differ"
+    return one
+
+
+@pytest.mark.parametrize("name", FUSED_CASES)
+def test_append_fused_into_attention_small_cases(H, name):
+    Hq, Hkv, D, q_len, ctx = SMALL[name]
+    b = W.make_batch(W.custom_spec(name, Hq, Hkv, D, q_len, ctx, seed=zlib.crc32(name.encode()) % 10007))
+    one = check_fused_step(H, b, name)
+    # and directly against the oracle: pools bit-exact, outputs within the stated tolerance
+    ref, kp, vp = oracle.run_batch(b)
+    gk, gv = one.pools_host()
+    assert np.array_equal(gk, kp) and np.array_equal(gv, vp)
+    check_attention(one.out_f64(), ref, b, tag=name + " fused")
+
+
+@pytest.mark.parametrize("idx", [1, 2, 3, 4])
+def test_append_fused_into_attention_full_size_configs(H, idx):
+    check_fused_step(H, W.make_batch(W.config_spec(idx)), f"config{idx}")
+
+
+def test_append_fused_into_attention_half_precision(H):
+    Hq, Hkv, D, q_len, ctx = SMALL["decode_long_ragged"]
+    check_fused_step(H, W.make_batch(W.custom_spec("fused16", Hq, Hkv, D, q_len, ctx, seed=5, dtype="fp16")), "fp16")
+
+
+def test_plan_object_reused_for_successive_batches(H):
+    """tc_plan_update: one plan object re-planned for a larger, then a smaller batch gives, on the GPU, the
+    bits a fresh plan gives (its device buffer grows once and is reused after)."""
+    import torch
+    shapes = [([40, 1, 1], [10, 300, 50]), ([700, 1, 1, 1, 1], [900, 9000, 50, 700, 2500]), ([1, 1], [77, 1030])]
+    batches = [W.make_batch(W.custom_spec(f"upd{i}", 32, 8, 128, q, c, seed=60 + i, num_blocks=4096)) for i, (q, c) in enumerate(shapes)]
+    fresh = []
+    for b in batches:
+        db = H.DeviceBatch(b)
+        db.step()
+        fresh.append(H.to_host(db.out).copy())
+    db0 = H.DeviceBatch(batches[0])
+    plan = db0.plan
+    for b, want in zip(batches, fresh):
+        db = H.DeviceBatch(b)
+        plan.update(db.pool, b.q_start, b.spec.ctx_len, b.block_table)
+        assert plan.info.total_q == b.total_q
+        db.plan.destroy()
+        db.plan = plan
+        db.workspace = torch.empty(max(plan.workspace_bytes, 16), dtype=torch.uint8, device="cuda:0")
+        db.step()
+        assert np.array_equal(H.to_host(db.out), want)
+    # an invalid batch leaves an empty plan: its calls are no-ops
+    import paper_2508_01989_amd as tc
+    bad = batches[2].block_table.copy()
+    bad[0, 0] = -3
+    with pytest.raises(tc.TcError) as e:
+        plan.update(db.pool, batches[2].q_start, batches[2].spec.ctx_len, bad)
+    assert e.value.status == tc.TC_ERR_BLOCK and plan.info.total_q == 0
+    db.out.fill_(7)
+    db.step()
+    torch.cuda.synchronize()
+    assert (H.to_host(db.out) == 7).all()
+    db.plan = None
 
 
 def test_graph_replays_equal_the_eager_step(H):
