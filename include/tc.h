@@ -195,6 +195,18 @@ tc_status tc_mixed_attention_append(const tc_plan *plan, const tc_kv_pool *pool,
                                     const void *v_new, void *out, float scale, void *workspace, size_t workspace_bytes,
                                     void *stream);
 
+/* tc_mixed_attention for callers that cannot allocate device memory (code under HIP graph capture,
+ * tight serving loops, harnesses that forbid it) and so cannot bring a workspace: the partial
+ * results go to a static array in device memory, 64 MiB, that every GPU the library runs on holds
+ * until the process ends.  The call allocates and frees nothing.  A plan whose
+ * tc_plan_workspace_bytes() exceeds 64 MiB is rejected with TC_ERR_WORKSPACE and nothing is
+ * launched.  All calls on one GPU share that GPU's array: calls that overlap in time race.  The
+ * array keeps what the last call left; no part of it has to start at zero (every partial result is
+ * written before it is read; the arrival counters live in the plan).  Output bit for bit that of
+ * tc_mixed_attention. */
+tc_status tc_mixed_attention_static(const tc_plan *plan, const tc_kv_pool *pool, const void *q, void *out, float scale,
+                                    void *stream);
+
 /* The same operation (paper Sec. 2.1) with the combination of partial results as a launch of its
  * own, for callers that time the parts or put other work between them (same arguments, checks and
  * errors).  tc_attention_partials runs the attention kernel without the in-kernel combination: rows

@@ -18,7 +18,7 @@ TC_BF16, TC_FP16 = 1, 2
 
 EXPORTS = ["tc_plan_create", "tc_plan_create_host", "tc_plan_update", "tc_plan_get_info", "tc_plan_copy_items",
            "tc_plan_workspace_bytes", "tc_plan_destroy", "tc_kv_append", "tc_mixed_attention", "tc_mixed_attention_append",
-           "tc_attention_partials", "tc_split_merge",
+           "tc_mixed_attention_static", "tc_attention_partials", "tc_split_merge",
            "tc_kv_gather", "tc_probe_mfma_loop", "tc_probe_stream_read",
            "tc_kv_transfer_bytes", "tc_kv_export", "tc_kv_import", "tc_status_str", "tc_last_error", "tc_version"]
 
@@ -74,6 +74,7 @@ def lib():
         L.tc_mixed_attention.argtypes = [vp, C.POINTER(tc_kv_pool), vp, vp, C.c_float, vp, C.c_size_t, vp]
         L.tc_attention_partials.argtypes = L.tc_mixed_attention.argtypes
         L.tc_mixed_attention_append.argtypes = [vp, C.POINTER(tc_kv_pool), vp, vp, vp, vp, C.c_float, vp, C.c_size_t, vp]
+        L.tc_mixed_attention_static.argtypes = [vp, C.POINTER(tc_kv_pool), vp, vp, C.c_float, vp]
         L.tc_probe_mfma_loop.argtypes = [C.c_int32, vp, C.c_size_t, vp]
         L.tc_probe_stream_read.argtypes = [vp, C.c_size_t, vp, vp]
         L.tc_split_merge.argtypes = [vp, C.POINTER(tc_kv_pool), vp, vp, C.c_size_t, vp]
@@ -202,6 +203,10 @@ def tc_mixed_attention_append(plan: Plan, pool: tc_kv_pool, q, k_new, v_new, out
         workspace_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
     _check(lib().tc_mixed_attention_append(plan.handle, C.byref(pool), _ptr(q), _ptr(k_new), _ptr(v_new), _ptr(out),
                                            C.c_float(scale), _ptr(workspace), workspace_bytes, _stream(stream)))
+
+
+def tc_mixed_attention_static(plan: Plan, pool: tc_kv_pool, q, out, scale, stream=None):
+    _check(lib().tc_mixed_attention_static(plan.handle, C.byref(pool), _ptr(q), _ptr(out), C.c_float(scale), _stream(stream)))
 
 
 def tc_probe_mfma_loop(iters, sink, stream=None):

@@ -70,6 +70,19 @@ tc_status tc_mixed_attention_append(const tc_plan *plan, const tc_kv_pool *pool,
                          "tc_mixed_attention_append launch");
 }
 
+tc_status tc_mixed_attention_static(const tc_plan *plan, const tc_kv_pool *pool, const void *q, void *out, float scale, void *stream) {
+    tc_status st = check_runnable(plan, pool);
+    if (st != TC_OK) return st;
+    if (plan->T == 0) return TC_OK;
+    void *scratch = nullptr;
+    size_t scratch_bytes = 0;
+    if (int err = tc::static_scratch(plan->device, &scratch, &scratch_bytes)) return device_result(err, "static scratch of this GPU");
+    if (plan->workspace_bytes() > scratch_bytes)
+        return fail(TC_ERR_WORKSPACE, "this batch needs more scratch than the static array holds (64 MiB): use tc_mixed_attention with a workspace");
+    return attention(plan, pool, q, nullptr, nullptr, out, scale, scratch, scratch_bytes, tc::kLaunchFused, stream,
+                     "tc_mixed_attention_static launch");
+}
+
 tc_status tc_attention_partials(const tc_plan *plan, const tc_kv_pool *pool, const void *q, void *out, float scale,
                                 void *workspace, size_t workspace_bytes, void *stream) {
     return attention(plan, pool, q, nullptr, nullptr, out, scale, workspace, workspace_bytes, tc::kLaunchAttention, stream,

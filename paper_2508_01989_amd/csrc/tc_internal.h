@@ -27,7 +27,7 @@ constexpr int kPrefillTileTokens = 64;  // KV tokens per LDS tile of the prefill
 constexpr int kNumCu = 256;         // compute units the work list is balanced for
 constexpr int kMigrateLayers = 64;  // layers one migration launch covers (their pool pointers travel as kernel arguments)
 constexpr int kMaxLayers = 4096;
-constexpr int kMaxDevices = 64;     // per-device state (function attributes) is kept for this many GPUs
+constexpr int kMaxDevices = 64;     // per-device state (function attributes, the static scratch) is kept for this many GPUs
 
 // Field indices of work items (see tc_plan_copy_items in tc.h).
 enum { PF_SEQ, PF_KVH, PF_POS0, PF_NPOS, PF_QROW0, PF_CTX, PF_PAGEOFF, PF_NPAGES };
@@ -126,6 +126,8 @@ constexpr int kLaunchAttention = 1, kLaunchMerge = 2, kLaunchFused = 4;
 // k_new / v_new non-null: the attention kernel also stores the batch's new K/V rows (see tc_mixed_attention_append).
 int launch_attention(const tc_plan *p, const tc_kv_pool *pool, const void *q, const void *k_new, const void *v_new, void *out,
                      float scale, void *workspace, int launches, void *stream);
+// The device address of this GPU's static scratch array and its size (tc_mixed_attention_static).
+int static_scratch(int device, void **ptr, size_t *bytes);
 // Pool <-> transfer buffer copy of the pages [page0, page0 + n_pages) of the plan, all layers.
 int launch_kv_migrate(const tc_plan *p, bool import, int page0, int n_pages, int num_layers, void *const *k_pools,
                       void *const *v_pools, void *buffer, void *stream);

@@ -1490,4 +1490,33 @@ int launch_attention(const tc_plan *p, const tc_kv_pool *pool, const void *q, co
     return p->D == 128 ? launch_attention_d<128, Bf16>(p, A, launches, st) : launch_attention_d<64, Bf16>(p, A, launches, st);
 }
 
+// ------------------------------------------------------------------------------------
+// Static scratch: a workspace for callers that cannot allocate
+// ------------------------------------------------------------------------------------
+// Partial results of split KV ranges for tc_mixed_attention_static.  Every GPU the library runs on holds
+// its own copy of the array, at its own address, until the process ends.  Host code never uses the
+// array's name as an address: the device address is asked for once per device and kept.
+constexpr size_t kStaticScratchBytes = (size_t)64 << 20;
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+
+int static_scratch(int device, void **ptr, size_t *bytes) {
+    static std::atomic<void *> address[kMaxDevices];
+    *bytes = kStaticScratchBytes;
+    *ptr = nullptr;
+    if (device < 0 || device >= kMaxDevices) return (int)hipErrorInvalidDevice;
+    void *a = address[device].load(std::memory_order_acquire);
+    if (!a) {
+        int current = -1;
+        hipError_t e = hipGetDevice(&current);
+        if (e != hipSuccess) return (int)e;
+        if (current != device) return (int)hipErrorInvalidDevice;  // the address is that of the current device's copy
+        e = hipGetSymbolAddress(&a, HIP_SYMBOL(scratch));
+        if (e != hipSuccess) return (int)e;
+        if (!a) return (int)hipErrorInvalidSymbol;
+        address[device].store(a, std::memory_order_release);
+    }
+    *ptr = a;
+    return 0;
+}
+
 }  // namespace tc

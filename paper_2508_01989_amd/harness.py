@@ -8,7 +8,7 @@ import numpy as np
 import torch
 
 from . import (TC_BF16, TC_FP16, Plan, make_pool, tc_attention_partials, tc_kv_append, tc_kv_gather, tc_mixed_attention,
-               tc_mixed_attention_append, tc_split_merge)
+               tc_mixed_attention_append, tc_mixed_attention_static, tc_split_merge)
 
 
 def to_dev(a: np.ndarray, device="cuda:0") -> torch.Tensor:
@@ -84,6 +84,10 @@ class DeviceBatch:
         """The same pass with the append done by the attention call (tc_mixed_attention_append)."""
         tc_mixed_attention_append(self.plan, self.pool, self.q, self.k_new, self.v_new, self.out, self.spec.scale, self.workspace,
                                   self.plan.workspace_bytes, stream=self.stream)
+
+    def attention_static(self):
+        """tc_mixed_attention with the library's static scratch array in place of the workspace."""
+        tc_mixed_attention_static(self.plan, self.pool, self.q, self.out, self.spec.scale, stream=self.stream)
 
     def gather(self, s):
         sp = self.spec
