@@ -185,8 +185,9 @@ tc_status tc_mixed_attention(const tc_plan *plan, const tc_kv_pool *pool, const 
 
 /* tc_kv_append and tc_mixed_attention of the same batch in one call (paper Sec. 2.1: the new tokens'
  * K and V are cached as part of the iteration that computes them).  The new row of every decode
- * sequence is stored into the pool by the one wavefront that runs the sequence's last KV split, before
- * that wavefront fetches the page it lies in: no second launch touches it and no other wavefront reads it.  The
+ * sequence is taken from k_new / v_new by the one wavefront that runs the sequence's last KV split,
+ * used from registers and stored into the pool by that wavefront: no second launch touches it and no
+ * other wavefront reads it.  The
  * rows of prefill chunks are read by many workgroups of the attention kernel, which may not wait for
  * one another, so they are stored first by the append kernel, restricted to the chunks' rows: a batch
  * of decodes is one launch, a mixed batch two.  Pools and outputs are bit for bit those of

@@ -16,13 +16,18 @@ FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared", "-fno
          "-Wall", "-Wno-unused-command-line-argument"]
 
 
-def build(verbose: bool = False, extra=()) -> str:
+TRACE_LIB = os.path.join(HERE, "libtc_mi355x_trace.so")  # the same library with per-workgroup time stamps in the attention kernel
+
+
+def build(verbose: bool = False, extra=(), trace: bool = False) -> str:
     hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
+    if trace:
+        extra = [*extra, "-DTC_WG_TRACE"]
     cmd = [hipcc, *FLAGS, *extra, "-I", os.path.join(ROOT, "include"), "-I", CSRC]
     for s in SOURCES:
         path = os.path.join(CSRC, s)
         cmd += (["-x", "hip", path] if s.endswith(".cpp") else ["-x", "hip", path])
-    cmd += ["-o", LIB]
+    cmd += ["-o", TRACE_LIB if trace else LIB]
     if verbose:
         print(" ".join(cmd))
     r = subprocess.run(cmd, capture_output=True, text=True)
@@ -32,7 +37,7 @@ def build(verbose: bool = False, extra=()) -> str:
         raise RuntimeError("hipcc failed:\n" + err)
     if verbose and err.strip():
         print(err)
-    return LIB
+    return TRACE_LIB if trace else LIB
 
 
 def build_sched(verbose: bool = False) -> str:
@@ -51,4 +56,7 @@ def build_sched(verbose: bool = False) -> str:
 
 if __name__ == "__main__":
     print(build_sched(verbose=True))
-    print(build(verbose=True, extra=[a for a in sys.argv[1:] if a.startswith("-")]))
+    if "--trace" in sys.argv[1:]:
+        print(build(verbose=True, trace=True))
+    else:
+        print(build(verbose=True, extra=[a for a in sys.argv[1:] if a.startswith("-")]))

@@ -941,27 +941,38 @@ struct DecodePage {  // K and V of one page, in MFMA A-operand registers
 
 // KV pages are read exactly once per launch, by one wavefront: stream them past the caches.
 // When the attention kernel also does the append, the newest token of a decode sequence (index tn of the
-// last page of its last KV split, pool block `id`) is stored into the pool by the wavefront that runs that
-// split, before the wavefront fetches the page: the lane that stores a piece is the lane that reads it back
-// (same (token, piece) and (element, token group) ownership as in decode_fetch), the store is complete
-// before the fetch is issued, and no other wavefront reads or writes that slot, so nothing else has to be ordered.
+// last page of its last KV split, pool block `id`) has not been stored when that page is fetched: the
+// wavefront that runs the split takes the token's K and V from this iteration's rows, puts them in the place of
+// what the fetch found in that slot, and stores them into the pool.  No other wavefront reads or writes the
+// slot, so nothing has to be ordered.  (Storing first and fetching the page afterwards measured 2 % slower.)
 template <int D>
-__device__ __forceinline__ void decode_store_new_token(const AttnArgs &A, int kvh, int id, int qrow, int tn, int j, int g) {
+__device__ __forceinline__ void decode_take_new_token(const AttnArgs &A, int kvh, int id, int qrow, int tn, int j, int g,
+                                                      DecodePage<D> &st) {
     const int64_t tile_elems = (int64_t)kBlock * D;
     uint16_t *kb = A.k_pool + ((int64_t)id * A.Hkv + kvh) * tile_elems;
     uint16_t *vb = A.v_pool + ((int64_t)id * A.Hkv + kvh) * tile_elems;
     const uint16_t *kn = A.k_new + ((int64_t)qrow * A.Hkv + kvh) * D;
     const uint16_t *vn = A.v_new + ((int64_t)qrow * A.Hkv + kvh) * D;
-    if (j == tn) {  // K: the 8-element pieces 4 kk + g of token j
+    if (j == tn) {
 #pragma unroll
-        for (int kk = 0; kk < D / 32; kk++)
-            *reinterpret_cast<u32x4 *>(kb + ((4 * kk + g) * kBlock + tn) * 8) = *reinterpret_cast<const u32x4 *>(kn + (4 * kk + g) * 8);
+        for (int kk = 0; kk < D / 32; kk++) {
+            const u32x4 w = *reinterpret_cast<const u32x4 *>(kn + (4 * kk + g) * 8);
+            st.k[kk] = w;
+            *reinterpret_cast<u32x4 *>(kb + ((4 * kk + g) * kBlock + tn) * 8) = w;
+        }
     }
-    if (g == (tn >> 2)) {  // V: tokens 4 g .. 4 g + 3 of the elements 16 c + j
+    if (g == (tn >> 2)) {
+        const int e = tn & 3;
 #pragma unroll
-        for (int c = 0; c < D / 16; c++) vb[(16 * c + j) * kBlock + v_slot(tn)] = vn[16 * c + j];
+        for (int c = 0; c < D / 16; c++) {
+            const uint32_t val = vn[16 * c + j];
+            u32x2 w = st.v[c];
+            const uint32_t keep = (e & 1) ? 0x0000FFFFu : 0xFFFF0000u, put = (e & 1) ? val << 16 : val;
+            if (e >> 1) w[1] = (w[1] & keep) | put; else w[0] = (w[0] & keep) | put;
+            st.v[c] = w;
+            vb[(16 * c + j) * kBlock + v_slot(tn)] = (uint16_t)val;
+        }
     }
-    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
 }
 
 template <int D>
@@ -1058,7 +1069,6 @@ __device__ void decode_item(const AttnArgs &A, const int32_t *__restrict__ it, f
         const int page0 = t0 / kBlock;
         const int n_pg = (n_tok + kBlock - 1) / kBlock;  // 1..64
         const int32_t *pages = A.pages + it[DC_PAGEOFF] + page0;
-        if (takes_new) decode_store_new_token<D>(A, kvh, pages[n_pg - 1], qrow, (n_tok - 1) & (kBlock - 1), j, g);
         const int my_page = pages[min(lane, n_pg - 1)];  // lane i holds the id of page i of the split
 
         x8 qreg[KS];
@@ -1096,6 +1106,8 @@ __device__ void decode_item(const AttnArgs &A, const int32_t *__restrict__ it, f
                 if (cur < n_pg) {
                     const int nxt = cur + NS - 1;
                     if (nxt < n_pg) decode_fetch<D>(A, kvh, __builtin_amdgcn_readlane(my_page, nxt), j, g, st[(u + NS - 1) % NS]);
+                    if (takes_new && cur == n_pg - 1)
+                        decode_take_new_token<D>(A, kvh, __builtin_amdgcn_readlane(my_page, cur), qrow, (n_tok - 1) & (kBlock - 1), j, g, st[u]);
                     decode_consume<D, E>(A, st[u], qreg, n_tok - cur * kBlock, g, o, m_run, l_run);
                 }
             }
@@ -1175,6 +1187,13 @@ __device__ void decode_item(const AttnArgs &A, const int32_t *__restrict__ it, f
     if (lane == 0) __hip_atomic_store(counter, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
 
+#ifdef TC_WG_TRACE
+// Tracing build (python -m paper_2508_01989_amd.build --trace): every workgroup of the attention kernel leaves the time
+// it started, the time its prefill pieces were done and the time it ended (100 MHz counter), and where it ran.
+constexpr int kTraceWorkgroups = 16384;
+__device__ long long g_wg_trace[kTraceWorkgroups * 4];
+#endif
+
 struct AttnScalars {
     int n_prefill, n_decode;
     int Hq, Hkv, G;
@@ -1198,6 +1217,10 @@ __global__ void __launch_bounds__(WAVES * 64, WAVES == kMixedWaves ? 1 : kDecode
                            const int32_t *__restrict__ wg_first, const int32_t *__restrict__ decode,
                            const int32_t *__restrict__ merge, int32_t *counters, float *ws, const AttnScalars sc) {
     extern __shared__ __align__(16) char lds[];
+#ifdef TC_WG_TRACE
+    const long long t_start = __builtin_amdgcn_s_memrealtime();
+    long long t_mid = t_start;
+#endif
     AttnArgs A;
     A.k_pool = k_pool; A.v_pool = v_pool; A.q = q; A.k_new = k_new; A.v_new = v_new; A.out = out; A.pages = pages; A.prefill = prefill;
     A.pieces = pieces; A.wg_first = wg_first; A.decode = decode; A.merge = merge; A.counters = counters;
@@ -1222,8 +1245,11 @@ __global__ void __launch_bounds__(WAVES * 64, WAVES == kMixedWaves ? 1 : kDecode
         // the decode items fill whole workgroups (padding items at the end of some): every wave gets one
         if (idx < A.n_decode) decode_item<D, E, NS>(A, decode + (int64_t)idx * kItemInts, reinterpret_cast<float *>(lds), WAVES);
     }
+#ifdef TC_WG_TRACE
+    t_mid = __builtin_amdgcn_s_memrealtime();
+#endif
     if constexpr (WAVES == kMixedWaves) {
-        if (A.queue < 0) return;
+        if (A.queue >= 0) {
         // Decode queue (the launch has no more workgroups than the chip has compute units, all resident from the
         // start).  The decode items are handed out in units of one workgroup's worth (WAVES items, teams included)
         // through a counter: the workgroups launched for the decode branch draw from the start, the prefill
@@ -1249,7 +1275,21 @@ __global__ void __launch_bounds__(WAVES * 64, WAVES == kMixedWaves ? 1 : kDecode
             __hip_atomic_store(next_unit, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
             __hip_atomic_store(gone, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         }
+        }
     }
+#ifdef TC_WG_TRACE
+    __syncthreads();
+    if (threadIdx.x == 0 && blockIdx.x < kTraceWorkgroups) {
+        unsigned hw, xcc;
+        asm volatile("s_getreg_b32 %0, hwreg(HW_REG_HW_ID)" : "=s"(hw));
+        asm volatile("s_getreg_b32 %0, hwreg(HW_REG_XCC_ID)" : "=s"(xcc));
+        long long *t = g_wg_trace + (long long)blockIdx.x * 4;
+        t[0] = t_start;
+        t[1] = __builtin_amdgcn_s_memrealtime();
+        t[2] = ((long long)xcc << 32) | hw;
+        t[3] = (((int)blockIdx.x < sc.n_prefill) ? 0 : 1) | ((t_mid - t_start) << 8);
+    }
+#endif
 }
 
 // ------------------------------------------------------------------------------------
@@ -1520,3 +1560,11 @@ int static_scratch(int device, void **ptr, size_t *bytes) {
 }
 
 }  // namespace tc
+
+#ifdef TC_WG_TRACE
+// Tracing build only: copy the first n int64 of the workgroup trace of the latest attention launch to HOST memory.
+extern "C" int tc_debug_wg_trace(long long *dst, int n) {
+    (void)hipDeviceSynchronize();
+    return (int)hipMemcpyFromSymbol(dst, HIP_SYMBOL(tc::g_wg_trace), (size_t)n * sizeof(long long));
+}
+#endif

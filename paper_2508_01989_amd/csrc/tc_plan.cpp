@@ -257,6 +257,9 @@ tc_status build_plan(tc_plan *p, const tc_kv_pool *pool, const tc_batch *b) {
     // Wave slots left free hold padding items (no tokens).
     const int W = w.blocks.empty() ? kDecodeWaves : kMixedWaves;
     p->split_tokens = choose_split(decode_tokens * Hkv);
+#ifdef TC_TUNE
+    if (const char *e = std::getenv("TC_TUNE_SPLIT")) p->split_tokens = std::atoi(e);
+#endif
     w.runs.clear();
     for (int s = 0; s < S; s++) {
         if (p->q_start[s + 1] - p->q_start[s] != 1) continue;
