@@ -997,9 +997,14 @@ __device__ __forceinline__ void decode_consume(const AttnArgs &A, DecodePage<D> 
     using x4 = typename E::x4;
     using el = typename E::t;
     constexpr int KS = D / 32, MT = D / 16;
-    f32x4 s = f32x4{0.f, 0.f, 0.f, 0.f};
+    // two accumulators: the second half of the head dimension does not wait for the first
+    f32x4 s = f32x4{0.f, 0.f, 0.f, 0.f}, s_hi = f32x4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-    for (int kk = 0; kk < KS; kk++) s = E::mfma16(__builtin_bit_cast(x8, st.k[kk]), qreg[kk], s);
+    for (int kk = 0; kk < KS / 2; kk++) {
+        s = E::mfma16(__builtin_bit_cast(x8, st.k[kk]), qreg[kk], s);
+        s_hi = E::mfma16(__builtin_bit_cast(x8, st.k[kk + KS / 2]), qreg[kk + KS / 2], s_hi);
+    }
+    s += s_hi;
     if (n_valid < kBlock) {  // the split ends inside this page: mask scores, make V finite
 #pragma unroll
         for (int r = 0; r < 4; r++) s[r] = (4 * g + r < n_valid) ? s[r] : -INFINITY;
@@ -1013,26 +1018,41 @@ __device__ __forceinline__ void decode_consume(const AttnArgs &A, DecodePage<D> 
             st.v[c] = w;
         }
     }
-    float mx = fmaxf(fmaxf(s[0], s[1]), fmaxf(s[2], s[3]));
-    mx = fmaxf(mx, xor_lanes(mx, 16));
-    mx = half_swap_max(mx);
-    const float m_new = fmaxf(m_run, mx * A.scale_log2);
-    const float alpha = fast_exp2(m_run - m_new);
-    m_run = m_new;
+    // As in the prefill branch the reference maximum of a head column (log2 domain) is kept while it serves: the page's
+    // probabilities are computed against it as it is, and only when a lane's sum of its four gets out of hand (one
+    // of them is above 2^11; the test also catches the first page, whose reference is -1e30, and NaN) does the wave, in
+    // a uniform branch, find the page's true maxima, move the reference of the columns that need it, bring O and l
+    // to it and compute the probabilities again.  The common page has no reduction across lanes and no rescaling:
+    // beside a prefill chunk the decode branch runs on few compute units and is bound by its own instructions.
     x4 pb;
     float psum = 0.f;
 #pragma unroll
     for (int r = 0; r < 4; r++) {
-        const float pv = fast_exp2(__builtin_fmaf(s[r], A.scale_log2, -m_new));
+        const float pv = fast_exp2(__builtin_fmaf(s[r], A.scale_log2, -m_run));
         psum += pv;
         pb[r] = (el)pv;
     }
-    l_run = l_run * alpha + psum;
+    if (__builtin_amdgcn_ballot_w64(!(psum <= kSumLimit)) != 0) {
+        float mx = fmaxf(fmaxf(s[0], s[1]), fmaxf(s[2], s[3]));
+        mx = fmaxf(mx, xor_lanes(mx, 16));
+        mx = half_swap_max(mx);
+        const float m_new = next_reference_max(m_run, mx * A.scale_log2);
+        const float alpha = fast_exp2(m_run - m_new);
+        m_run = m_new;
+        l_run *= alpha;
 #pragma unroll
-    for (int c = 0; c < MT; c++) {
-        o[c] *= alpha;
-        o[c] = E::mfma16k16(__builtin_bit_cast(x4, st.v[c]), pb, o[c]);
+        for (int c = 0; c < MT; c++) o[c] *= alpha;
+        psum = 0.f;
+#pragma unroll
+        for (int r = 0; r < 4; r++) {
+            const float pv = fast_exp2(__builtin_fmaf(s[r], A.scale_log2, -m_new));
+            psum += pv;
+            pb[r] = (el)pv;
+        }
     }
+    l_run += psum;
+#pragma unroll
+    for (int c = 0; c < MT; c++) o[c] = E::mfma16k16(__builtin_bit_cast(x4, st.v[c]), pb, o[c]);
 }
 
 // The splits of one (sequence, KV head) that share a workgroup form a team (consecutive waves): the

@@ -4,7 +4,6 @@
 #include <algorithm>
 #include <chrono>
 #include <cmath>
-#include <cstdlib>
 #include <cstring>
 #include <new>
 
@@ -89,10 +88,8 @@ static void choose_prefill_cuts(std::vector<PlanRowBlock> &blocks, int Hkv, int6
     }
 }
 
-// Pieces of a batch whose row blocks number about as many as the compute units (a large chunk on a
-// prefill-heavy instance: each block would be one workgroup on one unit, and since the KV range grows with
-// the position the last block sweeps far longer than the first while the decode branch waits for freed
-// units).  The row blocks of a KV head, heaviest first, are laid end to end and cut into `bins` runs of equal
+// Pieces of a batch whose row blocks would leave a good part of the chip empty (between a quarter and three
+// quarters of the compute units: a mid-sized chunk).  The row blocks of a KV head, heaviest first, are laid end to end and cut into `bins` runs of equal
 // cost; each run is one workgroup, which sweeps its pieces one after the other.  A block that straddles a cut
 // becomes pieces of two (rarely more) workgroups.  The same cuts are used for every KV head.
 static void level_prefill(std::vector<PlanRowBlock> &blocks, std::vector<PlanPiece> &pieces, int bins) {
@@ -199,10 +196,11 @@ tc_status build_plan(tc_plan *p, const tc_kv_pool *pool, const tc_batch *b) {
         }
     }
     std::stable_sort(w.blocks.begin(), w.blocks.end(), [](const PlanRowBlock &x, const PlanRowBlock &y) { return x.cost > y.cost; });
-    // Three regimes by the number of prefill items (row blocks x KV heads) against the compute units:
-    //   few (at most a quarter):  cut each item's KV range so that more units work on the chunk
-    //   about as many (up to 4x): level the sweeps over a fixed number of workgroups, leaving units to the decode branch
-    //   many:                     one workgroup per item; the hardware hands them out heaviest first
+    // Regimes by the number of prefill items (row blocks x KV heads) against the compute units:
+    //   at most a quarter:        cut each item's KV range so that more units work on the chunk
+    //   up to three quarters:     level the sweeps over a fixed number of workgroups, leaving units to the decode branch
+    //   up to as many:            one workgroup per item, the decode items drawn from a queue by the units that finish early
+    //   more:                     one workgroup per item; the hardware hands them out heaviest first
     w.pieces.clear();
     const int64_t n_items = (int64_t)w.blocks.size() * Hkv, slots = kNumCu;
     const int64_t decode_bytes = decode_tokens * Hkv * D * 4;
@@ -212,25 +210,19 @@ tc_status build_plan(tc_plan *p, const tc_kv_pool *pool, const tc_batch *b) {
     bool queue = false;
     if (n_items > 0 && n_items * 4 <= slots) choose_prefill_cuts(w.blocks, Hkv, decode_bytes);
     if (n_items * 4 > slots && n_items <= 4 * slots) {
-        double tiles = 0, idle = 0;  // idle: what the units of the lighter row blocks would wait for the heaviest, in tiles
-        for (const PlanRowBlock &x : w.blocks) { tiles += x.n_tiles; idle += w.blocks[0].n_tiles - x.n_tiles; }
-        const double tile_us = kTileUs * (D / 128.0);
-        const double t_prefill = tiles * Hkv * tile_us, t_idle = idle * Hkv * tile_us, t_decode = (double)decode_bytes / (kDecodeCuGBs * 1e3);
         queue = decode_tokens > 0 && n_items <= slots;
-        // When the decode branch is about as much work as the lighter blocks' units would idle, the queue fills that
-        // time and the chunk runs uncut, one row block per workgroup.  With little or no decode work the sweeps are levelled
-        // instead (over as many workgroups as leave the decode branch the units it needs to finish with the chunk).
-        bool level = t_decode < 0.5 * t_idle;
-#ifdef TC_TUNE
-        if (const char *e = std::getenv("TC_TUNE_LEVEL")) level = std::atoi(e) != 0;
-#endif
-        if (level) {
+        // Row blocks that fill the chip (more than three quarters of the units) run uncut, one per workgroup: the
+        // queue lets the units of the lighter blocks carry the decode branch while the heavier ones still sweep, and
+        // cutting measured slower there, with or without decodes (partial results and a second start per workgroup
+        // cost more than the uneven sweeps).  Fewer row blocks are levelled over as many workgroups as leave the
+        // decode branch the units it needs to finish with the chunk, so that the whole chip works on the batch.
+        if (n_items * 4 <= 3 * slots) {
+            double tiles = 0;
+            for (const PlanRowBlock &x : w.blocks) tiles += x.n_tiles;
+            const double t_prefill = tiles * Hkv * kTileUs * (D / 128.0), t_decode = (double)decode_bytes / (kDecodeCuGBs * 1e3);
             const int cu_decode = decode_tokens ? std::max(1, (int)std::lround(slots * t_decode / (t_decode + t_prefill))) : 0;
             const int64_t by_units = std::max<int64_t>(1, (slots - std::min<int64_t>(cu_decode, slots / 2)) / Hkv);
             n_wg_per_head = (int)std::max<int64_t>(1, std::min<int64_t>(by_units, (int64_t)tiles / kMinBinTiles));
-#ifdef TC_TUNE
-            if (const char *e = std::getenv("TC_TUNE_BINS")) n_wg_per_head = std::atoi(e);
-#endif
             level_prefill(w.blocks, w.pieces, n_wg_per_head);
             queue = decode_tokens > 0;
         }
@@ -257,9 +249,6 @@ tc_status build_plan(tc_plan *p, const tc_kv_pool *pool, const tc_batch *b) {
     // Wave slots left free hold padding items (no tokens).
     const int W = w.blocks.empty() ? kDecodeWaves : kMixedWaves;
     p->split_tokens = choose_split(decode_tokens * Hkv);
-#ifdef TC_TUNE
-    if (const char *e = std::getenv("TC_TUNE_SPLIT")) p->split_tokens = std::atoi(e);
-#endif
     w.runs.clear();
     for (int s = 0; s < S; s++) {
         if (p->q_start[s + 1] - p->q_start[s] != 1) continue;

@@ -193,10 +193,10 @@ def check_work_list(tc, sp, table, nb):
         if 256 % Hkv == 0:
             assert np.all(heads == wg_of_piece % Hkv)
         tiles_of_wg = np.bincount(wg_of_piece, weights=(pc[:, 2] - pc[:, 1]), minlength=n_wg)
-        levelled = 256 < 4 * len(pf) <= 16 * 256 and len(pc) > len(pf)
+        levelled = 256 < 4 * len(pf) <= 3 * 256
         if not levelled:      # one piece per workgroup, most tiles first (uncut items, or few items whose KV ranges are cut)
             assert n_wg == len(pc) and np.all(np.diff(tiles_of_wg[::Hkv]) <= 0)
-        else:                 # about as many items as compute units and little decode work: every KV head has the same runs, of nearly equal cost (tiles + 3 per piece)
+        else:                 # items for a quarter to three quarters of the compute units: every KV head has the same runs, of nearly equal cost (tiles + 3 per piece)
             assert n_wg % Hkv == 0 and n_wg <= 256
             cost_of_wg = tiles_of_wg + 3 * np.bincount(wg_of_piece, minlength=n_wg)
             per_head = cost_of_wg.reshape(-1, Hkv)
@@ -298,8 +298,10 @@ def test_work_list_covers_the_batch_exactly(tc, idx):
     ("ragged chunk, G=5", 10, 2, [77, 1], [1500, 40], True),
     ("small chunk under a long decode phase", 32, 8, [128] + [1] * 256, [2048] + [3000] * 256, False),
     ("short context", 32, 8, [128], [100], False),
-    ("large chunk alone: levelled", 32, 8, [2048], [4096], True),
-    ("large chunk, few decodes: levelled, decode queue", 32, 8, [2048] + [1] * 4, [4096] + [500] * 4, True),
+    ("mid-sized chunk alone: levelled", 32, 8, [1024], [4096], True),
+    ("mid-sized chunk, decodes: levelled, decode queue", 32, 8, [1024] + [1] * 40, [4096] + [900] * 40, True),
+    ("chunk that fills the chip, alone: uncut", 32, 8, [2048], [4096], False),
+    ("chunk that fills the chip, decodes: uncut, decode queue", 32, 8, [1800] + [1] * 40, [4096] + [900] * 40, False),
 ])
 def test_small_prefill_batches_are_cut_into_kv_pieces(tc, name, Hq, Hkv, q_len, ctx, cut):
     sp = W.custom_spec(name, Hq, Hkv, 128, q_len, ctx)
