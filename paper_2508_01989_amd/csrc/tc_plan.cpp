@@ -214,12 +214,16 @@ tc_status build_plan(tc_plan *p, const tc_kv_pool *pool, const tc_batch *b) {
         // Row blocks that fill the chip (more than three quarters of the units) run uncut, one per workgroup: the
         // queue lets the units of the lighter blocks carry the decode branch while the heavier ones still sweep, and
         // cutting measured slower there, with or without decodes (partial results and a second start per workgroup
-        // cost more than the uneven sweeps).  Fewer row blocks are levelled over as many workgroups as leave the
-        // decode branch the units it needs to finish with the chunk, so that the whole chip works on the batch.
-        if (n_items * 4 <= 3 * slots) {
-            double tiles = 0;
-            for (const PlanRowBlock &x : w.blocks) tiles += x.n_tiles;
-            const double t_prefill = tiles * Hkv * kTileUs * (D / 128.0), t_decode = (double)decode_bytes / (kDecodeCuGBs * 1e3);
+        // cost more than the uneven sweeps).  Fewer row blocks leave units empty: with a decode branch of some
+        // weight those units carry it from the start (decode workgroups and the queue) and the blocks again run
+        // uncut; with little or no decode work the sweeps are levelled over the whole chip instead.
+        double tiles = 0;
+        for (const PlanRowBlock &x : w.blocks) tiles += x.n_tiles;
+        const double tile_us = kTileUs * (D / 128.0);
+        const double t_sweep = w.blocks[0].n_tiles * tile_us;  // the heaviest block's
+        const double t_decode_alone = decode_tokens ? std::max(16.0, (double)decode_bytes / 5.0e6) : 0.0;
+        if (n_items * 4 <= 3 * slots && t_decode_alone < 0.25 * t_sweep) {
+            const double t_prefill = tiles * Hkv * tile_us, t_decode = (double)decode_bytes / (kDecodeCuGBs * 1e3);
             const int cu_decode = decode_tokens ? std::max(1, (int)std::lround(slots * t_decode / (t_decode + t_prefill))) : 0;
             const int64_t by_units = std::max<int64_t>(1, (slots - std::min<int64_t>(cu_decode, slots / 2)) / Hkv);
             n_wg_per_head = (int)std::max<int64_t>(1, std::min<int64_t>(by_units, (int64_t)tiles / kMinBinTiles));

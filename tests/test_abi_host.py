@@ -193,7 +193,7 @@ def check_work_list(tc, sp, table, nb):
         if 256 % Hkv == 0:
             assert np.all(heads == wg_of_piece % Hkv)
         tiles_of_wg = np.bincount(wg_of_piece, weights=(pc[:, 2] - pc[:, 1]), minlength=n_wg)
-        levelled = 256 < 4 * len(pf) <= 3 * 256
+        levelled = 256 < 4 * len(pf) <= 3 * 256 and len(pc) > len(pf)   # (a mid-sized chunk beside a heavy decode branch runs uncut)
         if not levelled:      # one piece per workgroup, most tiles first (uncut items, or few items whose KV ranges are cut)
             assert n_wg == len(pc) and np.all(np.diff(tiles_of_wg[::Hkv]) <= 0)
         else:                 # items for a quarter to three quarters of the compute units: every KV head has the same runs, of nearly equal cost (tiles + 3 per piece)
@@ -299,7 +299,8 @@ def test_work_list_covers_the_batch_exactly(tc, idx):
     ("small chunk under a long decode phase", 32, 8, [128] + [1] * 256, [2048] + [3000] * 256, False),
     ("short context", 32, 8, [128], [100], False),
     ("mid-sized chunk alone: levelled", 32, 8, [1024], [4096], True),
-    ("mid-sized chunk, decodes: levelled, decode queue", 32, 8, [1024] + [1] * 40, [4096] + [900] * 40, True),
+    ("mid-sized chunk, few decodes: levelled, decode queue", 32, 8, [1024] + [1] * 4, [4096] + [900] * 4, True),
+    ("mid-sized chunk, many decodes: uncut, decode queue", 32, 8, [1024] + [1] * 64, [4096] + [2300] * 64, False),
     ("chunk that fills the chip, alone: uncut", 32, 8, [2048], [4096], False),
     ("chunk that fills the chip, decodes: uncut, decode queue", 32, 8, [1800] + [1] * 40, [4096] + [900] * 40, False),
 ])

@@ -121,12 +121,13 @@ SMALL = {
     "cut_g1_head_dim_64": (4, 4, 64, [100, 1], [900, 30]),
     "cut_eight_pieces": (32, 8, 128, [64], [5000]),
     "cut_chunk_at_unaligned_offset": (16, 4, 128, [50, 1], [1111, 700]),
-    # row blocks for a quarter to three quarters of the compute units: their sweeps are levelled over workgroups that run
-    # several pieces and combine them in the kernel, alone and beside decodes (which are then drawn from a queue); row
-    # blocks that fill the chip run uncut and the decode items are drawn from the queue by the units that finish early
+    # row blocks for a quarter to three quarters of the compute units: alone or beside a light decode branch their sweeps
+    # are levelled over workgroups that run several pieces and combine them in the kernel (the decodes are then drawn
+    # from a queue); beside a heavier decode branch they run uncut and the free units draw decode items from the start;
+    # row blocks that fill the chip run uncut and the decode items are drawn by the units that finish early
     "levelled_chunk_alone": (32, 8, 128, [700], [900]),
-    "levelled_chunk_few_decodes": (16, 4, 128, [1100, 1, 1], [300, 2500, 31]),
-    "levelled_chunk_and_decodes": (32, 8, 128, [520] + [1] * 24, [200] + [1500, 40, 2100, 900, 3300, 64] * 4),
+    "levelled_chunk_few_decodes": (16, 4, 128, [1100, 1, 1], [4000, 200, 31]),
+    "queue_mid_chunk_heavy_decodes": (32, 8, 128, [520] + [1] * 24, [200] + [1500, 40, 2100, 900, 3300, 64] * 4),
     "queue_chunk_fills_the_chip": (32, 8, 128, [1600] + [1] * 12, [320] + [1500, 40, 2100, 9000, 3300, 64] * 2),
 }
 
@@ -329,7 +330,7 @@ def test_two_launch_form_equals_the_single_call(H):
     assert e.value.status == tc.TC_ERR_NULL
 
 
-FUSED_CASES = ["levelled_chunk_few_decodes", "levelled_chunk_and_decodes", "queue_chunk_fills_the_chip", "decode_page_boundaries", "decode_split_boundaries", "decode_long_ragged", "decode_more_than_64_partials",
+FUSED_CASES = ["levelled_chunk_few_decodes", "queue_mid_chunk_heavy_decodes", "queue_chunk_fills_the_chip", "decode_page_boundaries", "decode_split_boundaries", "decode_long_ragged", "decode_more_than_64_partials",
                "teams_g16_with_prefill", "teams_d64_ragged", "two_prefill_segments_and_decodes", "gqa_g5", "head_dim_64",
                "several_row_blocks_mid_context", "cut_small_chunk_long_context", "decode_single_token_context"]
 
