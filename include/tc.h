@@ -184,13 +184,12 @@ tc_status tc_mixed_attention(const tc_plan *plan, const tc_kv_pool *pool, const 
                              void *workspace, size_t workspace_bytes, void *stream);
 
 /* tc_kv_append and tc_mixed_attention of the same batch in one call (paper Sec. 2.1: the new tokens'
- * K and V are cached as part of the iteration that computes them).  The new row of every decode
- * sequence is taken from k_new / v_new by the one wavefront that runs the sequence's last KV split,
- * used from registers and stored into the pool by that wavefront: no second launch touches it and no
- * other wavefront reads it.  The
- * rows of prefill chunks are read by many workgroups of the attention kernel, which may not wait for
- * one another, so they are stored first by the append kernel, restricted to the chunks' rows: a batch
- * of decodes is one launch, a mixed batch two.  Pools and outputs are bit for bit those of
+ * K and V are cached as part of the iteration that computes them).  A batch of decodes is ONE launch:
+ * the wavefront that runs a sequence's last KV split takes the new token's K and V from k_new / v_new
+ * (they replace, in registers, what the page fetch found in that slot), and the last workgroups of the
+ * same launch store the rows into the pool; nobody waits for anybody.  The rows of a prefill chunk are
+ * read by many workgroups of the attention kernel, which may not wait for one another, so a batch
+ * with a chunk is the two launches of the two calls.  Pools and outputs are bit for bit those of
  * tc_kv_append followed by tc_mixed_attention. */
 tc_status tc_mixed_attention_append(const tc_plan *plan, const tc_kv_pool *pool, const void *q, const void *k_new,
                                     const void *v_new, void *out, float scale, void *workspace, size_t workspace_bytes,

@@ -63,9 +63,13 @@ tc_status tc_mixed_attention_append(const tc_plan *plan, const tc_kv_pool *pool,
     const size_t need = plan->workspace_bytes();
     if (need > 0 && (!workspace || workspace_bytes < need)) return fail(TC_ERR_WORKSPACE, "workspace missing or too small");
     if (!(scale > 0.f) || scale > 3.0e38f) return fail(TC_ERR_ARG, "scale must be positive and finite");
-    // the rows of prefill chunks are read by many workgroups: they are stored first, by the append kernel
-    st = device_result(tc::launch_kv_append(plan, pool, k_new, v_new, true, stream), "tc_mixed_attention_append launch");
-    if (st != TC_OK) return st;
+    // A batch with a prefill chunk: the chunk's rows are read by many workgroups of the attention kernel, which may not
+    // wait for one another, so all rows are stored first, by the append kernel (the two calls in one).  A batch of
+    // decodes: one launch, whose last workgroups store the rows while the grid drains.
+    if (plan->n_pieces > 0) {
+        st = device_result(tc::launch_kv_append(plan, pool, k_new, v_new, false, stream), "tc_mixed_attention_append launch");
+        if (st != TC_OK) return st;
+    }
     return device_result(tc::launch_attention(plan, pool, q, k_new, v_new, out, scale, need ? workspace : nullptr, tc::kLaunchFused, stream),
                          "tc_mixed_attention_append launch");
 }

@@ -940,28 +940,23 @@ struct DecodePage {  // K and V of one page, in MFMA A-operand registers
 };
 
 // KV pages are read exactly once per launch, by one wavefront: stream them past the caches.
-// When the attention kernel also does the append, the newest token of a decode sequence (index tn of the
-// last page of its last KV split, pool block `id`) has not been stored when that page is fetched: the
-// wavefront that runs the split takes the token's K and V from this iteration's rows, puts them in the place of
-// what the fetch found in that slot, and stores them into the pool.  No other wavefront reads or writes the
-// slot, so nothing has to be ordered.  (Storing first and fetching the page afterwards measured 2 % slower.)
+// When the attention kernel also does the append (a batch of decodes: tc_mixed_attention_append), the newest
+// token of a sequence (index tn of the last page of its last KV split) may not be in the pool yet when that
+// page is fetched: the rows are stored by the last workgroups of the same launch (append_decode_rows),
+// and nobody waits for them.  The wavefront that runs the split therefore takes the token's K and V from this
+// iteration's rows and puts them in the place of what the fetch found in that slot.  (Storing the token from
+// here, scattered through a launch that streams K/V at the HBM limit, cost 40-60 us on 512 sequences where the
+// append kernel needs 14, and so did storing them from workgroups at the front of the launch; from workgroups at its
+// back, which run while the grid drains and after nearly every page has been read, they cost less than the launch they replace.)
 template <int D>
-__device__ __forceinline__ void decode_take_new_token(const AttnArgs &A, int kvh, int id, int qrow, int tn, int j, int g,
-                                                      DecodePage<D> &st) {
-    const int64_t tile_elems = (int64_t)kBlock * D;
-    uint16_t *kb = A.k_pool + ((int64_t)id * A.Hkv + kvh) * tile_elems;
-    uint16_t *vb = A.v_pool + ((int64_t)id * A.Hkv + kvh) * tile_elems;
+__device__ __forceinline__ void decode_take_new_token(const AttnArgs &A, int kvh, int qrow, int tn, int j, int g, DecodePage<D> &st) {
     const uint16_t *kn = A.k_new + ((int64_t)qrow * A.Hkv + kvh) * D;
     const uint16_t *vn = A.v_new + ((int64_t)qrow * A.Hkv + kvh) * D;
-    if (j == tn) {
+    if (j == tn) {  // K: this lane holds the 8-element pieces 4 kk + g of token j
 #pragma unroll
-        for (int kk = 0; kk < D / 32; kk++) {
-            const u32x4 w = *reinterpret_cast<const u32x4 *>(kn + (4 * kk + g) * 8);
-            st.k[kk] = w;
-            *reinterpret_cast<u32x4 *>(kb + ((4 * kk + g) * kBlock + tn) * 8) = w;
-        }
+        for (int kk = 0; kk < D / 32; kk++) st.k[kk] = *reinterpret_cast<const u32x4 *>(kn + (4 * kk + g) * 8);
     }
-    if (g == (tn >> 2)) {
+    if (g == (tn >> 2)) {  // V: this lane holds tokens 4 g .. 4 g + 3 of the elements 16 c + j
         const int e = tn & 3;
 #pragma unroll
         for (int c = 0; c < D / 16; c++) {
@@ -970,7 +965,31 @@ __device__ __forceinline__ void decode_take_new_token(const AttnArgs &A, int kvh
             const uint32_t keep = (e & 1) ? 0x0000FFFFu : 0xFFFF0000u, put = (e & 1) ? val << 16 : val;
             if (e >> 1) w[1] = (w[1] & keep) | put; else w[0] = (w[0] & keep) | put;
             st.v[c] = w;
-            vb[(16 * c + j) * kBlock + v_slot(tn)] = (uint16_t)val;
+        }
+    }
+}
+
+// The append of a batch of decodes, done by the last workgroups of the attention launch: thread = (sequence, KV head,
+// 8-element piece) copies the piece of the new token's K and scatters the piece of its V (token-minor pool), four per
+// thread.  `segments`: the plan's append segments, one per sequence here (one token each).
+template <int D>
+__device__ __forceinline__ void append_decode_rows(const AttnArgs &A, const int32_t *__restrict__ segments, int n_rows, int wg) {
+    constexpr int CH = D / 8, kPerThread = 4;
+    const int total = n_rows * A.Hkv * CH;
+#pragma unroll
+    for (int i = 0; i < kPerThread; i++) {
+        const int x = (wg * kPerThread + i) * (int)blockDim.x + (int)threadIdx.x;
+        if (x < total) {
+            const int c = x % CH, h = (x / CH) % A.Hkv;
+            const int32_t *seg = segments + (int64_t)(x / (CH * A.Hkv)) * kAppendInts;
+            const int row = seg[0], tok = seg[2];
+            const int64_t tile = ((int64_t)seg[3] * A.Hkv + h) * (int64_t)(kBlock * D);
+            const int64_t src = ((int64_t)row * A.Hkv + h) * D + c * 8;
+            *reinterpret_cast<u32x4 *>(A.k_pool + tile + ((int64_t)c * kBlock + tok) * 8) = *reinterpret_cast<const u32x4 *>(A.k_new + src);
+            const u32x4 v = *reinterpret_cast<const u32x4 *>(A.v_new + src);
+            uint16_t *dst = A.v_pool + tile + (int64_t)(c * 8) * kBlock + v_slot(tok);
+#pragma unroll
+            for (int e = 0; e < 8; e++) dst[e * kBlock] = (uint16_t)(v[e >> 1] >> ((e & 1) * 16));
         }
     }
 }
@@ -1127,7 +1146,7 @@ __device__ void decode_item(const AttnArgs &A, const int32_t *__restrict__ it, f
                     const int nxt = cur + NS - 1;
                     if (nxt < n_pg) decode_fetch<D>(A, kvh, __builtin_amdgcn_readlane(my_page, nxt), j, g, st[(u + NS - 1) % NS]);
                     if (takes_new && cur == n_pg - 1)
-                        decode_take_new_token<D>(A, kvh, __builtin_amdgcn_readlane(my_page, cur), qrow, (n_tok - 1) & (kBlock - 1), j, g, st[u]);
+                        decode_take_new_token<D>(A, kvh, qrow, (n_tok - 1) & (kBlock - 1), j, g, st[u]);
                     decode_consume<D, E>(A, st[u], qreg, n_tok - cur * kBlock, g, o, m_run, l_run);
                 }
             }
@@ -1220,6 +1239,7 @@ struct AttnScalars {
     int fused;
     int queue;
     int n_partials;
+    int n_front, n_append_rows;  // a batch of decodes whose rows this launch stores: the workgroups (the last of the grid) that do it, rows
     float scale_log2;
 };
 
@@ -1235,7 +1255,8 @@ __global__ void __launch_bounds__(WAVES * 64, WAVES == kMixedWaves ? 1 : kDecode
                            const uint16_t *__restrict__ v_new, uint16_t *__restrict__ out, const int32_t *__restrict__ pages,
                            const int32_t *__restrict__ prefill, const int32_t *__restrict__ pieces,
                            const int32_t *__restrict__ wg_first, const int32_t *__restrict__ decode,
-                           const int32_t *__restrict__ merge, int32_t *counters, float *ws, const AttnScalars sc) {
+                           const int32_t *__restrict__ merge, const int32_t *__restrict__ append, int32_t *counters, float *ws,
+                           const AttnScalars sc) {
     extern __shared__ __align__(16) char lds[];
 #ifdef TC_WG_TRACE
     const long long t_start = __builtin_amdgcn_s_memrealtime();
@@ -1249,6 +1270,14 @@ __global__ void __launch_bounds__(WAVES * 64, WAVES == kMixedWaves ? 1 : kDecode
     A.n_prefill = sc.n_prefill; A.n_decode = sc.n_decode; A.Hq = sc.Hq; A.Hkv = sc.Hkv; A.G = sc.G; A.fused = sc.fused; A.queue = sc.queue;
     A.scale_log2 = sc.scale_log2;
     constexpr int NS = WAVES == kMixedWaves ? kMixedDecodeStages : kDecodeStages;
+    if constexpr (WAVES == kDecodeWaves) {
+        const int first_append_wg = (int)gridDim.x - sc.n_front;
+        if ((int)blockIdx.x >= first_append_wg) {
+            append_decode_rows<D>(A, append, sc.n_append_rows, (int)blockIdx.x - first_append_wg);
+            return;
+        }
+    }
+    const int wg = (int)blockIdx.x;
     if (WAVES == kMixedWaves && (int)blockIdx.x < A.n_prefill) {
         if constexpr (WAVES == kMixedWaves) {
             const int32_t *pc = pieces + (int64_t)wg_first[blockIdx.x] * kItemInts;
@@ -1261,7 +1290,7 @@ __global__ void __launch_bounds__(WAVES * 64, WAVES == kMixedWaves ? 1 : kDecode
         }
     } else if (WAVES != kMixedWaves || A.queue < 0) {
         const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-        const int idx = ((int)blockIdx.x - A.n_prefill) * WAVES + wave;
+        const int idx = (wg - A.n_prefill) * WAVES + wave;
         // the decode items fill whole workgroups (padding items at the end of some): every wave gets one
         if (idx < A.n_decode) decode_item<D, E, NS>(A, decode + (int64_t)idx * kItemInts, reinterpret_cast<float *>(lds), WAVES);
     }
@@ -1490,19 +1519,28 @@ static int allow_prefill_lds(int device) {
 
 template <int D, class E>
 static int launch_attention_d(const tc_plan *p, const AttnArgs &A, int launches, hipStream_t st) {
-    const int grid = (launches & (kLaunchAttention | kLaunchFused)) ? p->grid_blocks() : 0;
-    const AttnScalars sc = {A.n_prefill, A.n_decode, A.Hq, A.Hkv, A.G, A.fused, A.queue, p->n_partials, A.scale_log2};
+    int grid = (launches & (kLaunchAttention | kLaunchFused)) ? p->grid_blocks() : 0;
+    // A batch of decodes whose rows this launch stores: workgroups at the back of the grid do it (four (row, KV head,
+    // 8-element piece) units per thread).  A batch with a prefill chunk never gets here with k_new set (see launch_attention).
+    int n_front = 0;
+    if (grid > 0 && A.k_new && p->n_pieces == 0) {
+        const int64_t units = (int64_t)p->n_append * p->Hkv * (D / 8);
+        n_front = (int)((units + kDecodeWaves * 64 * 4 - 1) / (kDecodeWaves * 64 * 4));
+        grid += n_front;
+    }
+    const AttnScalars sc = {A.n_prefill, A.n_decode, A.Hq, A.Hkv, A.G, A.fused, A.queue, p->n_partials, n_front, p->n_append, A.scale_log2};
+    const int32_t *append = p->dev + p->off_append;
     if (grid > 0 && p->n_pieces > 0) {
         const int lds = PrefillCfg<D>::kLdsBytes;  // the decode workgroups of the launch need less, for any G
         static_assert(decode_team_lds_bytes(kMixedWaves, 16, D) <= (size_t)PrefillCfg<D>::kLdsBytes, "team buffers must fit the prefill tiles' LDS");
         if (int err = allow_prefill_lds<D, E>(p->device)) return err;
         mixed_attention_kernel<D, E, kMixedWaves><<<grid, kMixedWaves * 64, lds, st>>>(
-            A.k_pool, A.v_pool, A.q, A.k_new, A.v_new, A.out, A.pages, A.prefill, A.pieces, A.wg_first, A.decode, A.merge, A.counters,
-            A.ws_o, sc);
+            A.k_pool, A.v_pool, A.q, A.k_new, A.v_new, A.out, A.pages, A.prefill, A.pieces, A.wg_first, A.decode, A.merge, append,
+            A.counters, A.ws_o, sc);
     } else if (grid > 0) {
         mixed_attention_kernel<D, E, kDecodeWaves><<<grid, kDecodeWaves * 64, decode_team_lds_bytes(kDecodeWaves, p->G, D), st>>>(
-            A.k_pool, A.v_pool, A.q, A.k_new, A.v_new, A.out, A.pages, A.prefill, A.pieces, A.wg_first, A.decode, A.merge, A.counters,
-            A.ws_o, sc);
+            A.k_pool, A.v_pool, A.q, A.k_new, A.v_new, A.out, A.pages, A.prefill, A.pieces, A.wg_first, A.decode, A.merge, append,
+            A.counters, A.ws_o, sc);
     }
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return (int)e;
@@ -1524,8 +1562,9 @@ int launch_attention(const tc_plan *p, const tc_kv_pool *pool, const void *q, co
     A.k_pool = (uint16_t *)pool->k_pool;
     A.v_pool = (uint16_t *)pool->v_pool;
     A.q = (const uint16_t *)q;
-    A.k_new = (const uint16_t *)k_new;
-    A.v_new = (const uint16_t *)v_new;
+    // only a batch of decodes has its rows stored by the attention launch itself
+    A.k_new = p->n_pieces == 0 ? (const uint16_t *)k_new : nullptr;
+    A.v_new = p->n_pieces == 0 ? (const uint16_t *)v_new : nullptr;
     A.out = (uint16_t *)out;
     A.pages = p->dev + p->off_pages;
     A.prefill = p->dev + p->off_prefill;
