@@ -66,7 +66,7 @@ def test_hand_worked_cases():
             want = [tuple(int(x) for x in seg.split(":")) for seg in f[3].split()]
             got, n_pf = so.form_batch(int(f[0]), parse_queue(f[1]), [int(x) for x in f[2].split(",") if x])
             assert got == want and n_pf == int(f[4]), f
-    assert seen == {"ALG1": 5, "EST": 6, "ALG2": 6, "BATCH": 4}
+    assert seen == {"ALG1": 5, "EST": 6, "ALG2": 7, "BATCH": 4}
 
 
 @pytest.mark.parametrize("seed", range(20))
@@ -101,13 +101,20 @@ def test_decode_schedule_properties(seed):
     used = sum(r[2] for r in reqs) + int(rng.integers(0, 30))
     mark = int(rng.integers(0, used + 10))
     d = so.decode_schedule(so.D_HEAVY, reqs, slo, alpha, used, mark)
-    # D is a prefix of the requests ordered by (longest output first, lower index first) ...
-    order = sorted(range(n), key=lambda i: (-reqs[i][1], i))
-    assert d == order[:len(d)]
-    # ... and the shortest such prefix that brings usage to the watermark (or everything)
-    freed = list(itertools.accumulate(reqs[i][2] for i in order))
-    need = next((k + 1 for k, f in enumerate(freed) if used - f <= mark), n) if used > mark else 0
-    assert len(d) == need
+    # what the algorithm's loop guarantees, stated without ranking the requests: nobody is taken twice;
+    # whoever is taken has an output at least as long as whoever stays (equal lengths: the lower index is
+    # taken first), and the taken ones come out longest first ...
+    assert len(set(d)) == len(d)
+    before = lambda i, j: (reqs[i][1], -i) > (reqs[j][1], -j)
+    assert all(before(i, j) for i in d for j in range(n) if j not in d)
+    assert all(before(i, j) for i, j in zip(d, d[1:]))
+    # ... each one was taken while the instance was still above its watermark, and the taking stopped
+    # as soon as it was not (or nobody was left)
+    left = used
+    for i in d:
+        assert left > mark
+        left -= reqs[i][2]
+    assert left <= mark or len(d) == n
 
 
 @pytest.mark.parametrize("seed", range(30))
