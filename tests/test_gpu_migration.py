@@ -144,3 +144,56 @@ def test_runtime_argument_errors(H):
             fn(plan, pool, 0, [], [], buf, num_layers=0)
         assert e.value.status == tc.TC_ERR_ARG
     plan.destroy()
+
+
+def test_blocks_past_two_to_the_31_elements_of_a_pool(H):
+    """Export from and import into pools of 4.6 GB per tensor whose used blocks all lie past element 2^31
+    (block ids raised by 140 000; 8 KV heads, head_dim 128): the transfer buffer and the raised part of the
+    destination pools must be the oracle's, computed in small pools, and the part below must stay untouched."""
+    import paper_2508_01989_amd as tc
+    import torch
+    Hq, Hkv, D, L, shift = 32, 8, 128, 1, 140_000
+    kv_len = np.asarray([1, 17, 300, 4097, 16], np.int64)
+    S = len(kv_len)
+    print(f"[case] migrate_high_block_ids: kv_len={kv_len.tolist()} shift={shift}", flush=True)
+    spec = W.custom_spec("migrate_high_block_ids", Hq, Hkv, D, [1] * S, (kv_len - 1).tolist(), seed=77)
+    pages, off = oracle.transfer_pages(kv_len)
+    nb = int(off[-1]) + 5
+    table, table2 = other_table(kv_len, nb, 78), other_table(kv_len, nb, 79)
+    src = host_pools(spec, table, nb, kv_len, L, 80)
+    want_buf = oracle.kv_export([p[0] for p in src], [p[1] for p in src], Hkv, D, 16, table, kv_len)
+    want = [oracle.new_pool(nb, Hkv, D, fill=0x7FC0) for _ in range(L)]
+    oracle.kv_import([p[0] for p in want], [p[1] for p in want], Hkv, D, 16, table2, kv_len, want_buf)
+
+    def raised(t):
+        return np.where(t == W.TABLE_SENTINEL, t, t + shift).astype(np.int32)
+
+    block_elems = Hkv * 16 * D
+    n_low, n_all = shift * block_elems, (shift + nb) * block_elems
+    assert n_low > 2 ** 31
+
+    def big_pool(tail, fill):
+        t = torch.full((n_all,), fill, dtype=torch.int16, device="cuda:0")
+        if tail is not None:
+            t[n_low:] = H.to_dev(tail)
+        return t
+
+    q_start, ctx = np.arange(S + 1, dtype=np.int32), (kv_len - 1).astype(np.int32)
+    pool = tc.make_pool(Hq, Hkv, D, shift + nb)
+    plan, plan2 = tc.Plan(pool, q_start, ctx, raised(table)), tc.Plan(pool, q_start, ctx, raised(table2))
+    dk, dv = [big_pool(src[0][0], -1)], [big_pool(src[0][1], -1)]
+    buf = torch.full((want_buf.size,), 0x5A5A, dtype=torch.int16, device="cuda:0")
+    assert tc.tc_kv_transfer_bytes(plan, -1, L) == want_buf.size * 2
+    tc.tc_kv_export(plan, pool, -1, dk, dv, buf)
+    torch.cuda.synchronize()
+    assert np.array_equal(H.to_host(buf), want_buf), "transfer buffer differs from the oracle's"
+    del dk, dv
+    gk, gv = [big_pool(None, 0x7FC0)], [big_pool(None, 0x7FC0)]
+    tc.tc_kv_import(plan2, pool, -1, gk, gv, buf)
+    torch.cuda.synchronize()
+    for got, ref in ((gk[0], want[0][0]), (gv[0], want[0][1])):
+        assert bool((got[:n_low] == 0x7FC0).all()), "blocks below the raised ones were written"
+        assert np.array_equal(H.to_host(got[n_low:]), ref), "destination pool differs from the oracle's"
+    plan.destroy()
+    plan2.destroy()
+

@@ -480,6 +480,34 @@ def test_chunked_prefill_matches_one_shot_on_gpu(H):
     check_attention(got, ref, one, tag="chunked prefill")
 
 
+def test_blocks_past_two_to_the_31_elements_of_a_pool(H):
+    """A pool of 4.6 GB per tensor whose used blocks all lie past element 2^31: the oracle runs the batch in a
+    small pool, the GPU runs it with every block id raised by 140 000 (x 8 KV heads x 16 x 128 elements =
+    2.29e9).  Append (separate and inside the attention call), gather and attention must agree with the
+    oracle, and nothing below the raised blocks may be written."""
+    import dataclasses
+    import torch
+    shift = 140_000
+    small = W.make_batch(W.custom_spec("high_block_ids", 32, 8, 128, [300, 1, 1, 1], [700, 3000, 77, 20000], seed=4242))
+    assert shift * 8 * 16 * 128 > 2 ** 31
+    ref, kp, vp = oracle.run_batch(small)
+    table = np.where(small.block_table == W.TABLE_SENTINEL, small.block_table, small.block_table + shift).astype(np.int32)
+    big = dataclasses.replace(small, block_table=table, num_blocks=small.num_blocks + shift)
+    n_low = shift * 8 * 16 * 128
+    for fused in (False, True):
+        tag = f"high_block_ids fused={fused}"
+        print(f"[case] {tag}: blocks {big.num_blocks}, {big.num_blocks * 8 * 16 * 128 * 2 / 1e9:.1f} GB per pool", flush=True)
+        db = H.DeviceBatch(big)
+        db.step_fused() if fused else db.step()
+        check_attention(db.out_f64(), ref, small, tag=tag)
+        for pool, want in ((db.k_pool, kp), (db.v_pool, vp)):
+            assert bool((pool[:n_low] == -1).all()), f"{tag}: blocks below the raised ones were written"
+            assert np.array_equal(H.to_host(pool[n_low:]), want), f"{tag}: pool differs from the oracle's"
+        check_gather(db, small, range(small.spec.num_seqs), tag)
+        del db
+        torch.cuda.empty_cache()
+
+
 def test_empty_batch_and_runtime_argument_errors(H):
     import paper_2508_01989_amd as tc
     import torch
