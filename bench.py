@@ -77,24 +77,29 @@ def measure_ceilings(stream):
     src = torch.empty(n, dtype=torch.uint8, device="cuda:0")
     src.fill_(1)
     ev = [torch.cuda.Event(enable_timing=True) for _ in range(4)]
-    best_mfma, best_read = 0.0, 0.0
+    dst = torch.empty(n, dtype=torch.uint8, device="cuda:0")
+    best_mfma, best_read, best_copy = 0.0, 0.0, 0.0
     for _ in range(3):
         ev[0].record(stream)
         tc.tc_probe_mfma_loop(iters, sink, stream=stream)
         ev[1].record(stream)
         tc.tc_probe_stream_read(src, n, sink, stream=stream)
         ev[2].record(stream)
+        tc.tc_probe_stream_copy(src, dst, n, stream=stream)
+        ev[3].record(stream)
         torch.cuda.synchronize()
         best_mfma = max(best_mfma, 256 * 8 * iters * 4 * 32768.0 / (ev[0].elapsed_time(ev[1]) * 1e-3) / 1e12)
         best_read = max(best_read, n / (ev[1].elapsed_time(ev[2]) * 1e-3) / 1e9)
-    del src
+        best_copy = max(best_copy, 2 * n / (ev[2].elapsed_time(ev[3]) * 1e-3) / 1e9)
+    del src, dst
     torch.cuda.empty_cache()
-    return {"mfma_loop_TFLOPs": best_mfma, "stream_read_GBs": best_read,
-            "what": "tc_probe_mfma_loop (bare 32x32x16 bf16 MFMA loop, 8 waves per compute unit) and tc_probe_stream_read "
-                    "(non-temporal read of 2 GiB), best of 3, timed in this run"}
+    return {"mfma_loop_TFLOPs": best_mfma, "stream_read_GBs": best_read, "stream_copy_GBs": best_copy,
+            "what": "tc_probe_mfma_loop (bare 32x32x16 bf16 MFMA loop, 8 waves per compute unit), tc_probe_stream_read "
+                    "(non-temporal read of 2 GiB) and tc_probe_stream_copy (2 GiB copied, bytes read plus bytes written), "
+                    "best of 3, timed in this run"}
 
 
-def bench_migrate(steps, warmup):
+def bench_migrate(steps, warmup, ceilings=None):
     """Move `n_req` decode requests (lengths of the pure-decode configuration, its head shape) of a
     32-layer model: tc_kv_export into a transfer buffer, tc_kv_import into other blocks of a second
     set of pools.  Bytes counted: every page read once and written once, per direction."""
@@ -162,7 +167,10 @@ def bench_migrate(steps, warmup):
                          "export_GBs": moved / (exp_ms * 1e-3) / 1e9, "import_GBs": moved / (imp_ms * 1e-3) / 1e9,
                          "export_frac": moved / (exp_ms * 1e-3) / 1e9 / PEAK_HBM_GBS,
                          "import_frac": moved / (imp_ms * 1e-3) / 1e9 / PEAK_HBM_GBS,
-                         "algorithmic_bytes": moved}}
+                         "algorithmic_bytes": moved,
+                         **({"export_frac_of_measured_stream_copy": moved / (exp_ms * 1e-3) / 1e9 / ceilings["stream_copy_GBs"],
+                             "import_frac_of_measured_stream_copy": moved / (imp_ms * 1e-3) / 1e9 / ceilings["stream_copy_GBs"]}
+                            if ceilings else {})}}
 
 
 def cpu_baseline(batch, work, target_s=15.0):
@@ -407,8 +415,12 @@ def main():
         return
     common = {"n_gpus": 1, "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "data": "synthetic"}
     if args.workload == MIGRATE:
-        line = bench_migrate(args.steps, args.warmup)
+        stream = torch.cuda.Stream()
+        with torch.cuda.stream(stream):
+            ceilings = None if args.plain else measure_ceilings(stream)
+        line = bench_migrate(args.steps, args.warmup, ceilings)
         line.update(common)
+        line["measured_ceilings"] = ceilings
         print(json.dumps(line))
         return
     stream = torch.cuda.Stream()
@@ -428,7 +440,7 @@ def main():
         per = {}
         for name in others:
             if name == MIGRATE:
-                per[name] = bench_migrate(max(10, min(args.steps, 50)), max(2, min(args.warmup, 5)))
+                per[name] = bench_migrate(max(10, min(args.steps, 50)), max(2, min(args.warmup, 5)), ceilings)
                 continue
             per[name] = bench_workload(name, args.steps, args.warmup, stream, ceilings, 0 if args.no_cpu_baseline else 5.0,
                                        cold=args.cold or name == "prefill_heavy", graph=args.graph, exact_steps=False)

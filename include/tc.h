@@ -249,15 +249,19 @@ tc_status tc_kv_export(const tc_plan *plan, const tc_kv_pool *pool, int32_t seq,
 tc_status tc_kv_import(const tc_plan *plan, const tc_kv_pool *pool, int32_t seq, int32_t num_layers,
                        void *const *k_pools, void *const *v_pools, const void *buffer, void *stream);
 
-/* Measurement probes (no part of the method): two bare loops whose rate on the chip at hand is the
+/* Measurement probes (no part of the method): three bare loops whose rate on the chip at hand is the
  * practical ceiling the kernels above are compared with, next to the published peaks.  The caller times
  * them with events on `stream`.
  * tc_probe_mfma_loop: 256 workgroups of 8 wavefronts, each wavefront 4 * iters MFMA 32x32x16 bf16
  * (32768 flop each) on independent accumulators; sink: DEVICE, at least 512 KiB, receives one float per thread.
  * tc_probe_stream_read: reads `bytes` bytes of src (DEVICE, 16-byte aligned) once with non-temporal
- * loads; sink: DEVICE, at least 4 bytes. */
+ * loads; sink: DEVICE, at least 4 bytes.
+ * tc_probe_stream_copy: copies the first `bytes` bytes (rounded down to 16) of src to dst (both DEVICE, 16-byte
+ * aligned, not overlapping) with non-temporal loads and stores: the ceiling of tc_kv_export / tc_kv_import,
+ * which move every byte once in and once out. */
 tc_status tc_probe_mfma_loop(int32_t iters, void *sink, size_t sink_bytes, void *stream);
 tc_status tc_probe_stream_read(const void *src, size_t bytes, void *sink, void *stream);
+tc_status tc_probe_stream_copy(const void *src, void *dst, size_t bytes, void *stream);
 
 const char *tc_status_str(tc_status s);
 /* Text of the last error raised on the calling thread ("" if none). */

@@ -19,7 +19,7 @@ TC_BF16, TC_FP16 = 1, 2
 EXPORTS = ["tc_plan_create", "tc_plan_create_host", "tc_plan_update", "tc_plan_get_info", "tc_plan_copy_items",
            "tc_plan_workspace_bytes", "tc_plan_destroy", "tc_kv_append", "tc_mixed_attention", "tc_mixed_attention_append",
            "tc_mixed_attention_static", "tc_attention_partials", "tc_split_merge",
-           "tc_kv_gather", "tc_probe_mfma_loop", "tc_probe_stream_read",
+           "tc_kv_gather", "tc_probe_mfma_loop", "tc_probe_stream_read", "tc_probe_stream_copy",
            "tc_kv_transfer_bytes", "tc_kv_export", "tc_kv_import", "tc_status_str", "tc_last_error", "tc_version"]
 
 
@@ -77,6 +77,7 @@ def lib():
         L.tc_mixed_attention_static.argtypes = [vp, C.POINTER(tc_kv_pool), vp, vp, C.c_float, vp]
         L.tc_probe_mfma_loop.argtypes = [C.c_int32, vp, C.c_size_t, vp]
         L.tc_probe_stream_read.argtypes = [vp, C.c_size_t, vp, vp]
+        L.tc_probe_stream_copy.argtypes = [vp, vp, C.c_size_t, vp]
         L.tc_split_merge.argtypes = [vp, C.POINTER(tc_kv_pool), vp, vp, C.c_size_t, vp]
         L.tc_kv_gather.argtypes = [vp, C.POINTER(tc_kv_pool), C.c_int32, vp, vp, vp]
         L.tc_kv_transfer_bytes.argtypes = [vp, C.c_int32, C.c_int32]
@@ -215,6 +216,10 @@ def tc_probe_mfma_loop(iters, sink, stream=None):
 
 def tc_probe_stream_read(src, nbytes, sink, stream=None):
     _check(lib().tc_probe_stream_read(_ptr(src), int(nbytes), _ptr(sink), _stream(stream)))
+
+
+def tc_probe_stream_copy(src, dst, nbytes, stream=None):
+    _check(lib().tc_probe_stream_copy(_ptr(src), _ptr(dst), int(nbytes), _stream(stream)))
 
 
 def tc_attention_partials(plan: Plan, pool: tc_kv_pool, q, out, scale, workspace=None, workspace_bytes=None, stream=None):

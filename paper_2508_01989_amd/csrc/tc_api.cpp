@@ -111,6 +111,12 @@ tc_status tc_probe_stream_read(const void *src, size_t bytes, void *sink, void *
     return device_result(tc::launch_probe_stream(src, bytes, sink, stream), "tc_probe_stream_read launch");
 }
 
+tc_status tc_probe_stream_copy(const void *src, void *dst, size_t bytes, void *stream) {
+    if (!src || !dst) return fail(TC_ERR_NULL, "src or dst is NULL");
+    if (bytes < 16) return fail(TC_ERR_ARG, "nothing to copy");
+    return device_result(tc::launch_probe_copy(src, dst, bytes, stream), "tc_probe_stream_copy launch");
+}
+
 tc_status tc_kv_gather(const tc_plan *plan, const tc_kv_pool *pool, int32_t seq, void *k_out, void *v_out, void *stream) {
     tc_status st = check_runnable(plan, pool);
     if (st != TC_OK) return st;

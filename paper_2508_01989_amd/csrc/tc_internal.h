@@ -139,5 +139,6 @@ void free_plan_buffers(tc_plan *p);
 const char *hip_error_text(int err);
 int launch_probe_mfma(int iters, void *sink, void *stream);
 int launch_probe_stream(const void *src, size_t bytes, void *sink, void *stream);
+int launch_probe_copy(const void *src, void *dst, size_t bytes, void *stream);
 
 }  // namespace tc

@@ -7,6 +7,8 @@
 //                        sustains under that load
 //   probe_stream_kernel  a grid-strided read of a buffer with non-temporal 16-byte loads, four in
 //                        flight per thread: the streaming-read rate of HBM
+//   probe_copy_kernel    the same loop storing what it reads to a second buffer (non-temporal): the rate of
+//                        a plain device copy, the ceiling of the kernels that move every byte once in and once out
 #include <hip/hip_runtime.h>
 
 #include "tc_internal.h"
@@ -51,6 +53,20 @@ __global__ void __launch_bounds__(256) probe_stream_kernel(const probe_u32x4 *__
     if (acc == 0x9E3779B9u) sink[0] = acc;  // keeps the loads alive; practically never taken
 }
 
+__global__ void __launch_bounds__(256) probe_copy_kernel(const probe_u32x4 *__restrict__ src, probe_u32x4 *__restrict__ dst, size_t n16) {
+    const size_t stride = (size_t)gridDim.x * blockDim.x;
+    size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    for (; i + 3 * stride < n16; i += 4 * stride) {
+        const probe_u32x4 a = __builtin_nontemporal_load(src + i), b = __builtin_nontemporal_load(src + i + stride),
+                          c = __builtin_nontemporal_load(src + i + 2 * stride), d = __builtin_nontemporal_load(src + i + 3 * stride);
+        __builtin_nontemporal_store(a, dst + i);
+        __builtin_nontemporal_store(b, dst + i + stride);
+        __builtin_nontemporal_store(c, dst + i + 2 * stride);
+        __builtin_nontemporal_store(d, dst + i + 3 * stride);
+    }
+    for (; i < n16; i += stride) __builtin_nontemporal_store(__builtin_nontemporal_load(src + i), dst + i);
+}
+
 int launch_probe_mfma(int iters, void *sink, void *stream) {
     probe_mfma_kernel<<<kNumCu, 512, 0, (hipStream_t)stream>>>(iters, (float *)sink);
     return (int)hipGetLastError();
@@ -58,6 +74,11 @@ int launch_probe_mfma(int iters, void *sink, void *stream) {
 
 int launch_probe_stream(const void *src, size_t bytes, void *sink, void *stream) {
     probe_stream_kernel<<<kNumCu * 32, 256, 0, (hipStream_t)stream>>>((const probe_u32x4 *)src, bytes / 16, (uint32_t *)sink);
+    return (int)hipGetLastError();
+}
+
+int launch_probe_copy(const void *src, void *dst, size_t bytes, void *stream) {
+    probe_copy_kernel<<<kNumCu * 32, 256, 0, (hipStream_t)stream>>>((const probe_u32x4 *)src, (probe_u32x4 *)dst, bytes / 16);
     return (int)hipGetLastError();
 }
 
