@@ -276,6 +276,24 @@ __device__ __forceinline__ float load1(const float *p) {
 }
 __device__ __forceinline__ void stores_done() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); }
 
+// 16 bytes at a time, for the piece regions (133 KiB each): buffer loads and stores that carry the cache policy of
+// a device-scope atomic access (the sc1 bit; the access goes past the caches that are not coherent across the
+// device) without being atomic, which no 16-byte access can be.  Nothing needs them to be: a region is complete
+// before its arrival is counted, and is read only after the count is full.
+typedef uint32_t u32x4_t __attribute__((ext_vector_type(4)));
+constexpr int kCoherentAux = 16;  // sc1
+__device__ __forceinline__ __amdgpu_buffer_rsrc_t peer_window(const float *base, uint32_t bytes) {
+    return __builtin_amdgcn_make_buffer_rsrc(const_cast<float *>(base), 0, (int)bytes, 0x00020000);  // raw dwords, no stride
+}
+template <bool PEER>
+__device__ __forceinline__ f32x4 load4(__amdgpu_buffer_rsrc_t win, const float *base, uint32_t byte_off) {
+    if (!PEER) return *reinterpret_cast<const f32x4 *>(reinterpret_cast<const char *>(base) + byte_off);
+    return __builtin_bit_cast(f32x4, __builtin_amdgcn_raw_buffer_load_b128(win, (int)byte_off, 0, kCoherentAux));
+}
+__device__ __forceinline__ void peer_store4(__amdgpu_buffer_rsrc_t win, uint32_t byte_off, f32x4 v) {
+    __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(u32x4_t, v), win, (int)byte_off, 0, kCoherentAux);
+}
+
 // One output row (query head j of a decode sequence, or of one position of a cut prefill item) from its
 // ns partial results in workspace slots slot0 .. slot0 + ns - 1:
 //   out = sum_i 2^(m_i - m*) o_i / sum_i 2^(m_i - m*) l_i,   m* = max_i m_i,   partials in index order.
@@ -383,17 +401,19 @@ struct PiecePartial {
     static constexpr int kChunks = 4 * MT;
     static constexpr int kOFloats = kMixedWaves * kChunks * 64 * 4;  // = kPrefillRows * D
     static constexpr int kFloats = kOFloats + kPrefillRows * 2;
+    static constexpr uint32_t kBytes = (uint32_t)kFloats * sizeof(float);
+    static __device__ __forceinline__ uint32_t lane_offset(int wave, int lane) { return (uint32_t)((wave * kChunks * 64 + lane) * 4 * sizeof(float)); }
     static __device__ __forceinline__ void store(float *region, int wave, int lane, const f32x16 (&o)[MT], float m, float l, bool peer) {
         float *dst = region + ((int64_t)wave * kChunks * 64 + lane) * 4;
         float *ml = region + kOFloats + (wave * 32 + (lane & 31)) * 2;
         if (peer) {
+            const __amdgpu_buffer_rsrc_t win = peer_window(region, kBytes);
+            const uint32_t at = lane_offset(wave, lane);
 #pragma unroll
             for (int c = 0; c < MT; c++)
 #pragma unroll
-                for (int q = 0; q < 4; q++) {
-                    peer_store2(dst + (4 * c + q) * 256, o[c][4 * q], o[c][4 * q + 1]);
-                    peer_store2(dst + (4 * c + q) * 256 + 2, o[c][4 * q + 2], o[c][4 * q + 3]);
-                }
+                for (int q = 0; q < 4; q++)
+                    peer_store4(win, at + (4 * c + q) * 1024, f32x4{o[c][4 * q], o[c][4 * q + 1], o[c][4 * q + 2], o[c][4 * q + 3]});
             if (lane < 32) peer_store2(ml, m, l);
         } else {
 #pragma unroll
@@ -408,10 +428,21 @@ struct PiecePartial {
             }
         }
     }
-    // `first`: region of the item's piece 0; the K regions follow each other.
+    // `first`: region of the item's piece 0; the K regions follow each other.  The accumulators of piece i + 1 are
+    // requested before those of piece i are added, so that a piece's worth of loads is always in flight.
     template <bool PEER>
     static __device__ __forceinline__ void combine(const float *first, int k, int wave, int lane, f32x16 (&o)[MT], float &l) {
         const float *ml = first + kOFloats + (wave * 32 + (lane & 31)) * 2;
+        const __amdgpu_buffer_rsrc_t win = peer_window(first, (uint32_t)k * kBytes);
+        const uint32_t at = lane_offset(wave, lane);
+        auto fetch = [&](int i, f32x4 (&t)[kChunks], float2 &mli) {
+            mli = load2<PEER>(ml + (int64_t)i * kFloats);
+#pragma unroll
+            for (int ch = 0; ch < kChunks; ch++) t[ch] = load4<PEER>(win, first, (uint32_t)i * kBytes + at + ch * 1024);
+        };
+        f32x4 t_cur[kChunks], t_nxt[kChunks];
+        float2 ml_cur, ml_nxt;
+        fetch(0, t_cur, ml_cur);
         float m_star = -1e30f;
         for (int i = 0; i < k; i++) m_star = fmaxf(m_star, load2<PEER>(ml + (int64_t)i * kFloats).x);
 #pragma unroll
@@ -420,22 +451,16 @@ struct PiecePartial {
             for (int r = 0; r < 16; r++) o[c][r] = 0.f;
         l = 0.f;
         for (int i = 0; i < k; i++) {
-            const float *src = first + (int64_t)i * kFloats + ((int64_t)wave * kChunks * 64 + lane) * 4;
-            const float2 mli = load2<PEER>(ml + (int64_t)i * kFloats);
-            f32x16 t[MT];
+            if (i + 1 < k) fetch(i + 1, t_nxt, ml_nxt);
+            const float w = fast_exp2(ml_cur.x - m_star);
+            l += w * ml_cur.y;
 #pragma unroll
             for (int c = 0; c < MT; c++)
 #pragma unroll
-                for (int q = 0; q < 4; q++) {
-                    const float2 a = load2<PEER>(src + (4 * c + q) * 256), b = load2<PEER>(src + (4 * c + q) * 256 + 2);
-                    t[c][4 * q] = a.x; t[c][4 * q + 1] = a.y; t[c][4 * q + 2] = b.x; t[c][4 * q + 3] = b.y;
-                }
-            const float w = fast_exp2(mli.x - m_star);
-            l += w * mli.y;
+                for (int r = 0; r < 16; r++) o[c][r] += w * t_cur[4 * c + (r >> 2)][r & 3];
 #pragma unroll
-            for (int c = 0; c < MT; c++)
-#pragma unroll
-                for (int r = 0; r < 16; r++) o[c][r] += w * t[c][r];
+            for (int ch = 0; ch < kChunks; ch++) t_cur[ch] = t_nxt[ch];
+            ml_cur = ml_nxt;
         }
     }
 };
