@@ -253,7 +253,8 @@ __global__ void __launch_bounds__(256) kv_migrate_kernel(const MigratePools pool
 // ------------------------------------------------------------------------------------
 // Partial results that are combined inside the attention kernel cross from one compute unit to another
 // (possibly on another die, with an L2 cache of its own) while the kernel runs.  They are written and read
-// with device-scope atomic stores and loads (relaxed; 8 bytes each), which go past the caches that are not
+// with device-scope atomic stores and loads (relaxed; 8 bytes each; the large piece regions with 16-byte
+// accesses that carry the same cache policy, see peer_window), which go past the caches that are not
 // coherent across the device, so no cache has to be written back or invalidated as a whole: a release
 // and an acquire fence per piece (an L2 write-back and an L2 invalidate, by every wave) measured twice
 // the kernel time on a levelled 2048-token chunk.  Ordering is by the arrival counter: a writer waits
