@@ -508,6 +508,29 @@ def test_blocks_past_two_to_the_31_elements_of_a_pool(H):
         torch.cuda.empty_cache()
 
 
+def test_measurement_probes_run_and_the_copy_probe_copies(H):
+    """The probes compute nothing of the method; this only checks that they launch, that the copy probe's
+    destination equals its source (ragged length: the bytes past the last whole 16 stay untouched) and that bad
+    arguments are refused."""
+    import torch
+    import paper_2508_01989_amd as tc
+    n = (1 << 22) + 16 * 37 + 5
+    src = torch.randint(0, 255, (n,), dtype=torch.uint8, device="cuda:0")
+    dst = torch.full((n,), 7, dtype=torch.uint8, device="cuda:0")
+    tc.tc_probe_stream_copy(src, dst, n)
+    sink = torch.zeros(256 * 512, dtype=torch.float32, device="cuda:0")
+    tc.tc_probe_stream_read(src, n, sink)
+    tc.tc_probe_mfma_loop(10, sink)
+    torch.cuda.synchronize()
+    whole = n // 16 * 16
+    assert torch.equal(dst[:whole], src[:whole]) and bool((dst[whole:] == 7).all())
+    assert bool(torch.isfinite(sink).all())
+    with pytest.raises(tc.TcError):
+        tc.tc_probe_stream_copy(src, dst, 8)
+    with pytest.raises(tc.TcError):
+        tc.tc_probe_mfma_loop(0, sink)
+
+
 def test_empty_batch_and_runtime_argument_errors(H):
     import paper_2508_01989_amd as tc
     import torch
