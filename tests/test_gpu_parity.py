@@ -129,6 +129,13 @@ SMALL = {
     "levelled_chunk_few_decodes": (16, 4, 128, [1100, 1, 1], [4000, 200, 31]),
     "queue_mid_chunk_heavy_decodes": (32, 8, 128, [520] + [1] * 24, [200] + [1500, 40, 2100, 900, 3300, 64] * 4),
     "queue_chunk_fills_the_chip": (32, 8, 128, [1600] + [1] * 12, [320] + [1500, 40, 2100, 9000, 3300, 64] * 2),
+    # two thousand short decodes (contexts 0..40): workgroups packed with many small teams, padding items at the end
+    "two_thousand_tiny_decodes": (8, 2, 128, [1] * 2000, [(7 * i) % 41 for i in range(2000)]),
+    # contexts at the edges of the split rule: one split of exactly 1024 tokens, one more token, all waves' splits full, one more
+    "decode_split_rule_edges": (8, 2, 128, [1] * 6, [1023, 1024, 4095, 4096, 8191, 8192]),
+    "decode_split_rule_edges_beside_a_chunk": (8, 2, 128, [33] + [1] * 4, [5] + [1023, 1024, 8191, 8192]),
+    # the largest group of heads with the smaller head size, prefill and decode
+    "gqa_g16_head_dim_64": (16, 1, 64, [70, 1, 1], [40, 900, 17]),
 }
 
 
